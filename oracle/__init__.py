@@ -1,0 +1,184 @@
+"""Float64 CPU oracle for Skiparse-2D attention.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``skiparse_oracle.c`` (plain C, float64, OpenMP over independent query
+rows).  Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import this
+package; the GPU library never does, and this package never imports the GPU library.
+
+Array conventions: inputs are C-contiguous numpy arrays in the original layout ``[B][N][heads][D]``
+with dtype ``uint16`` (bfloat16 bit patterns), ``float32`` or ``float64``; attention outputs are
+``float64``.  Patterns: ``"token"`` (token-wise sparse attention) and ``"group"`` (group-wise sparse
+attention), Sec. 3.1 and Algorithm 1 of the OSP-Next paper.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "skiparse_oracle.c")
+_LIB = os.path.join(_HERE, "libskiparse_oracle.so")
+
+PATTERNS = {"token": 0, "group": 1}
+_DTYPES = {np.dtype(np.uint16): 0, np.dtype(np.float32): 1, np.dtype(np.float64): 2}
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (a second or two); returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i, i64, dbl, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+        lib.oracle_src_index.restype = i64
+        lib.oracle_src_index.argtypes = [i, i, i, i, i, i, i, i64]
+        lib.oracle_dst_index.restype = None
+        lib.oracle_dst_index.argtypes = [i, i, i, i, i, i64, ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i64)]
+        lib.oracle_permute.restype = i
+        lib.oracle_permute.argtypes = [vp, vp, i, i, i, i, i64, i, i]
+        lib.oracle_unpermute.restype = i
+        lib.oracle_unpermute.argtypes = [vp, vp, i, i, i, i, i64, i, i]
+        lib.oracle_attention.restype = i
+        lib.oracle_attention.argtypes = [vp, vp, vp, vp, i64, i64, i, i, dbl, i]
+        lib.oracle_skiparse_attention.restype = i
+        lib.oracle_skiparse_attention.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, dbl, i]
+        lib.oracle_skiparse_attention_rows.restype = i
+        lib.oracle_skiparse_attention_rows.argtypes = [vp, vp, vp, vp, i64, vp, i, i, i, i, i, i, i, i, dbl, i]
+        lib.oracle_masked_dense_attention.restype = i
+        lib.oracle_masked_dense_attention.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, dbl, i]
+        lib.oracle_num_threads.restype = i
+        lib.oracle_num_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise ValueError(f"oracle: {what} rejected its arguments or ran out of memory (code {rc})")
+
+
+def _dtype_code(*arrays: np.ndarray) -> int:
+    dt = arrays[0].dtype
+    for a in arrays:
+        if a.dtype != dt or not a.flags.c_contiguous:
+            raise ValueError("oracle inputs must share one dtype and be C-contiguous")
+    if dt not in _DTYPES:
+        raise ValueError(f"oracle: unsupported dtype {dt} (use uint16 bf16 bits, float32 or float64)")
+    return _DTYPES[dt]
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops of the oracle will use."""
+    return int(_load().oracle_num_threads())
+
+
+def src_index(pattern: str, s: int, T: int, H: int, W: int, p: int, q: int, j: int) -> int:
+    """Token index n of element j of the subsequence with spatial class (p, q) (Algorithm 1)."""
+    return int(_load().oracle_src_index(PATTERNS[pattern], s, T, H, W, p, q, j))
+
+
+def dst_index(pattern: str, s: int, T: int, H: int, W: int, n: int):
+    """(p, q, j) of token n: its spatial class and its position inside that subsequence."""
+    p, q, j = ctypes.c_int(), ctypes.c_int(), ctypes.c_int64()
+    _load().oracle_dst_index(PATTERNS[pattern], s, T, H, W, n, ctypes.byref(p), ctypes.byref(q), ctypes.byref(j))
+    return p.value, q.value, j.value
+
+
+def permute(x: np.ndarray, T: int, H: int, W: int, s: int, pattern: str) -> np.ndarray:
+    """[B][N][...] -> [s*s*B][N/s^2][...], rows moved verbatim (any dtype)."""
+    x = np.ascontiguousarray(x)
+    B, N = x.shape[0], x.shape[1]
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    row_bytes = x.strides[1]
+    y = np.empty((s * s * B, N // (s * s)) + x.shape[2:], dtype=x.dtype)
+    _check(_load().oracle_permute(_ptr(x), _ptr(y), B, T, H, W, row_bytes, s, PATTERNS[pattern]), "permute")
+    return y
+
+
+def unpermute(y: np.ndarray, T: int, H: int, W: int, s: int, pattern: str) -> np.ndarray:
+    """Inverse of :func:`permute`."""
+    y = np.ascontiguousarray(y)
+    B = y.shape[0] // (s * s)
+    N = T * H * W
+    if y.shape[0] != B * s * s or y.shape[1] * s * s != N:
+        raise ValueError("sparse-layout shape does not match the grid")
+    row_bytes = y.strides[1]
+    x = np.empty((B, N) + y.shape[2:], dtype=y.dtype)
+    _check(_load().oracle_unpermute(_ptr(y), _ptr(x), B, T, H, W, row_bytes, s, PATTERNS[pattern]), "unpermute")
+    return x
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float) -> np.ndarray:
+    """softmax(Q K^T * scale) V for every (batch, head); q,k,v are [nb][n][heads][D]."""
+    code = _dtype_code(q, k, v)
+    nb, n, heads, D = q.shape
+    out = np.empty(q.shape, dtype=np.float64)
+    _check(_load().oracle_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(out), nb, n, heads, D, float(scale), code), "attention")
+    return out
+
+
+def skiparse_attention(q, k, v, T: int, H: int, W: int, s: int, pattern: str, scale: float) -> np.ndarray:
+    """unpermute(attention(permute(q), permute(k), permute(v))), original layout in and out."""
+    code = _dtype_code(q, k, v)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    out = np.empty(q.shape, dtype=np.float64)
+    _check(
+        _load().oracle_skiparse_attention(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), code
+        ),
+        "skiparse_attention",
+    )
+    return out
+
+
+def skiparse_attention_rows(q, k, v, rows, T: int, H: int, W: int, s: int, pattern: str, scale: float) -> np.ndarray:
+    """Rows of :func:`skiparse_attention` for query positions rows[i] = (b, head, n) only -> [n_rows][D]."""
+    code = _dtype_code(q, k, v)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
+    out = np.empty((rows.shape[0], D), dtype=np.float64)
+    _check(
+        _load().oracle_skiparse_attention_rows(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(rows), rows.shape[0], _ptr(out), B, heads, T, H, W, D, s,
+            PATTERNS[pattern], float(scale), code,
+        ),
+        "skiparse_attention_rows",
+    )
+    return out
+
+
+def masked_dense_attention(q, k, v, T: int, H: int, W: int, s: int, pattern: str, scale: float) -> np.ndarray:
+    """Brute force: N x N attention with pairs of different spatial class masked out (tiny grids only)."""
+    code = _dtype_code(q, k, v)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    out = np.empty(q.shape, dtype=np.float64)
+    _check(
+        _load().oracle_masked_dense_attention(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), code
+        ),
+        "masked_dense_attention",
+    )
+    return out

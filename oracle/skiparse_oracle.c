@@ -1,0 +1,330 @@
+/*
+ * Skiparse-2D attention -- float64 CPU oracle.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition that the GPU library is checked against.  It shares no
+ * code, header, table or helper with the HIP path and must never be linked or called by it; only
+ * the tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ *
+ * What it computes (OSP-Next paper, Sec. 3.1 "Skiparse-2D Attention" and Algorithm 1 "Skiparse
+ * Rearrange"):
+ *   1. the token-wise / group-wise rearrangement of a (T,H,W) token grid into s*s subsequences,
+ *   2. ordinary softmax attention inside every subsequence (Sec. 3.1: interactions occur only inside
+ *      each sub-figure; Sec. 3.3: each subsequence performs global attention),
+ *   3. the inverse rearrangement.
+ * The method is a re-indexing followed by exact attention, so the oracle is that definition written
+ * out: two-pass softmax in float64, no tiling, no online rescaling.
+ *
+ * Layouts (Algorithm 1):
+ *   original  x[b][n][c]        n = (t*H + h)*W + w,  c = head*D + d     ("b (t h w) c")
+ *   sparse    y[sb][j][c]       sb = (p*s + q)*B + b                     ("(p q b) ...", batch fastest)
+ *                               j  = (t*Hs + hs)*Ws + ws, Hs = H/s, Ws = W/s
+ * Token-wise (Alg. 1, orig_to_tsa):  h = hs*s + p,  w = ws*s + q  -> subsequence (h mod s, w mod s).
+ * Group-wise (Alg. 1, orig_to_gsa):  the h axis splits as (h_outer, p, h_inner) with h_inner in [0,s):
+ *      h = (hs / s)*s*s + p*s + (hs mod s),  same for w with q -> subsequence (floor(h/s) mod s, floor(w/s) mod s).
+ *
+ * Element types: 0 = bfloat16 bit patterns (uint16), 1 = float32, 2 = float64.  Values are widened to
+ * float64 exactly before any arithmetic.
+ *
+ * All functions return 0 on success and a negative number on a bad argument.
+ */
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_TOKEN = 0, ORACLE_GROUP = 1 };
+enum { ORACLE_BF16 = 0, ORACLE_F32 = 1, ORACLE_F64 = 2 };
+
+static double load_elem(const void *base, int dtype, int64_t i)
+{
+    if (dtype == ORACLE_BF16) {
+        uint32_t bits = (uint32_t)((const uint16_t *)base)[i] << 16; /* bf16 = top half of an fp32 */
+        float f;
+        memcpy(&f, &bits, 4);
+        return (double)f;
+    }
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)base)[i];
+    return ((const double *)base)[i];
+}
+
+static int shape_ok(int B, int T, int H, int W, int s, int pattern)
+{
+    if (B < 1 || T < 1 || H < 1 || W < 1 || s < 1) return 0;
+    if (pattern == ORACLE_TOKEN) return H % s == 0 && W % s == 0;
+    if (pattern == ORACLE_GROUP) return H % (s * s) == 0 && W % (s * s) == 0;
+    return 0;
+}
+
+/* Alg. 1, sparse -> original direction: token index n of element j of spatial class (p,q). */
+int64_t oracle_src_index(int pattern, int s, int T, int H, int W, int p, int q, int64_t j)
+{
+    int Hs = H / s, Ws = W / s;
+    int64_t ws = j % Ws;
+    int64_t hs = (j / Ws) % Hs;
+    int64_t t = j / ((int64_t)Ws * Hs);
+    int64_t h, w;
+    (void)T;
+    if (pattern == ORACLE_TOKEN) {
+        h = hs * s + p;
+        w = ws * s + q;
+    } else {
+        h = (hs / s) * s * s + (int64_t)p * s + hs % s;
+        w = (ws / s) * s * s + (int64_t)q * s + ws % s;
+    }
+    return (t * H + h) * W + w;
+}
+
+/* Alg. 1, original -> sparse direction: token n belongs to class (p,q) and sits at position j there. */
+void oracle_dst_index(int pattern, int s, int T, int H, int W, int64_t n, int *p, int *q, int64_t *j)
+{
+    int Hs = H / s, Ws = W / s;
+    int64_t w = n % W;
+    int64_t h = (n / W) % H;
+    int64_t t = n / ((int64_t)W * H);
+    int64_t hs, ws;
+    (void)T;
+    if (pattern == ORACLE_TOKEN) {
+        *p = (int)(h % s);
+        *q = (int)(w % s);
+        hs = h / s;
+        ws = w / s;
+    } else {
+        *p = (int)((h / s) % s);
+        *q = (int)((w / s) % s);
+        hs = (h / (s * s)) * s + h % s;
+        ws = (w / (s * s)) * s + w % s;
+    }
+    *j = (t * Hs + hs) * Ws + ws;
+}
+
+/* y[sb][j][:] = x[b][src(sb,j)][:] on raw bytes; row_bytes = C * element size. */
+int oracle_permute(const void *x, void *y, int B, int T, int H, int W, int64_t row_bytes, int s, int pattern)
+{
+    if (!x || !y || row_bytes < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    int64_t N = (int64_t)T * H * W, Nsub = N / (s * s);
+    for (int p = 0; p < s; p++)
+        for (int q = 0; q < s; q++)
+            for (int b = 0; b < B; b++) {
+                int64_t sb = ((int64_t)p * s + q) * B + b;
+                for (int64_t j = 0; j < Nsub; j++) {
+                    int64_t n = oracle_src_index(pattern, s, T, H, W, p, q, j);
+                    memcpy((char *)y + (sb * Nsub + j) * row_bytes, (const char *)x + ((int64_t)b * N + n) * row_bytes,
+                           (size_t)row_bytes);
+                }
+            }
+    return 0;
+}
+
+/* x[b][src(sb,j)][:] = y[sb][j][:] */
+int oracle_unpermute(const void *y, void *x, int B, int T, int H, int W, int64_t row_bytes, int s, int pattern)
+{
+    if (!x || !y || row_bytes < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    int64_t N = (int64_t)T * H * W, Nsub = N / (s * s);
+    for (int p = 0; p < s; p++)
+        for (int q = 0; q < s; q++)
+            for (int b = 0; b < B; b++) {
+                int64_t sb = ((int64_t)p * s + q) * B + b;
+                for (int64_t j = 0; j < Nsub; j++) {
+                    int64_t n = oracle_src_index(pattern, s, T, H, W, p, q, j);
+                    memcpy((char *)x + ((int64_t)b * N + n) * row_bytes, (const char *)y + (sb * Nsub + j) * row_bytes,
+                           (size_t)row_bytes);
+                }
+            }
+    return 0;
+}
+
+/*
+ * One attention output row, plain definition:
+ *   S[j] = scale * sum_d Q[d]*K[j][d];  m = max_j S[j];  P[j] = exp(S[j]-m);  O[:] = sum_j P[j] V[j][:] / sum_j P[j]
+ * Key/value row j lives at element offset kv_off[j] (so that callers can walk a subsequence of a
+ * tensor in the original layout without copying it).  `scores` is scratch of n_keys doubles.
+ */
+static void attention_row(const void *q, int64_t q_off, const void *k, const void *v, const int64_t *kv_off, int64_t n_keys,
+                          int D, double scale, int dtype, double *scores, double *out)
+{
+    double m = -INFINITY;
+    for (int64_t j = 0; j < n_keys; j++) {
+        double acc = 0.0;
+        for (int d = 0; d < D; d++) acc += load_elem(q, dtype, q_off + d) * load_elem(k, dtype, kv_off[j] + d);
+        scores[j] = scale * acc;
+        if (scores[j] > m) m = scores[j];
+    }
+    double denom = 0.0;
+    for (int d = 0; d < D; d++) out[d] = 0.0;
+    for (int64_t j = 0; j < n_keys; j++) {
+        double pj = exp(scores[j] - m);
+        denom += pj;
+        for (int d = 0; d < D; d++) out[d] += pj * load_elem(v, dtype, kv_off[j] + d);
+    }
+    for (int d = 0; d < D; d++) out[d] /= denom;
+}
+
+/*
+ * Attention over a batch of independent sequences: q,k,v are [nb][n][heads][D] contiguous, out is
+ * float64 of the same shape.  Every (batch, head) pair is one softmax(Q K^T * scale) V.
+ */
+int oracle_attention(const void *q, const void *k, const void *v, double *out, int64_t nb, int64_t n, int heads, int D,
+                     double scale, int dtype)
+{
+    if (!q || !k || !v || !out || nb < 1 || n < 1 || heads < 1 || D < 1) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t C = (int64_t)heads * D;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)n);
+        int64_t *off = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+        if (!scores || !off) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 1)
+            for (int64_t b = 0; b < nb; b++)
+                for (int hd = 0; hd < heads; hd++) {
+                    for (int64_t j = 0; j < n; j++) off[j] = (b * n + j) * C + (int64_t)hd * D;
+                    for (int64_t i = 0; i < n; i++)
+                        attention_row(q, off[i], k, v, off, n, D, scale, dtype, scores, out + off[i]);
+                }
+        }
+        free(scores);
+        free(off);
+    }
+    return fail ? -2 : 0;
+}
+
+/*
+ * Skiparse-2D attention, inputs and float64 output in the ORIGINAL layout [B][N][heads][D]:
+ *   out = unpermute( attention( permute(q), permute(k), permute(v) ) )      (Sec. 3.1, Alg. 1)
+ * written exactly as that composition, with whole permuted copies.
+ */
+int oracle_skiparse_attention(const void *q, const void *k, const void *v, double *out, int B, int heads, int T, int H, int W,
+                              int D, int s, int pattern, double scale, int dtype)
+{
+    if (!q || !k || !v || !out || heads < 1 || D < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t esz = dtype == ORACLE_BF16 ? 2 : dtype == ORACLE_F32 ? 4 : 8;
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W, Nsub = N / (s * s);
+    size_t in_bytes = (size_t)(B * N * C * esz), out_bytes = (size_t)(B * N * C) * sizeof(double);
+    void *qp = malloc(in_bytes), *kp = malloc(in_bytes), *vp = malloc(in_bytes);
+    double *op = (double *)malloc(out_bytes);
+    int rc = -2;
+    if (qp && kp && vp && op) {
+        oracle_permute(q, qp, B, T, H, W, C * esz, s, pattern);
+        oracle_permute(k, kp, B, T, H, W, C * esz, s, pattern);
+        oracle_permute(v, vp, B, T, H, W, C * esz, s, pattern);
+        rc = oracle_attention(qp, kp, vp, op, (int64_t)B * s * s, Nsub, heads, D, scale, dtype);
+        if (rc == 0) rc = oracle_unpermute(op, out, B, T, H, W, C * (int64_t)sizeof(double), s, pattern);
+    }
+    free(qp);
+    free(kp);
+    free(vp);
+    free(op);
+    return rc;
+}
+
+/*
+ * Sampled mode for shapes whose full result is out of reach on a CPU: output rows of
+ * oracle_skiparse_attention for a list of (b, head, n) query positions only.  rows = [n_rows][3]
+ * int64, out = [n_rows][D] float64.  Each row attends to every token of its own subsequence,
+ * found through the same index maps; s = 1 gives sampled rows of full attention.
+ */
+int oracle_skiparse_attention_rows(const void *q, const void *k, const void *v, const int64_t *rows, int64_t n_rows, double *out,
+                                   int B, int heads, int T, int H, int W, int D, int s, int pattern, double scale, int dtype)
+{
+    if (!q || !k || !v || !rows || !out || n_rows < 0 || heads < 1 || D < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W, Nsub = N / (s * s);
+    for (int64_t r = 0; r < n_rows; r++)
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= heads || rows[3 * r + 2] < 0 ||
+            rows[3 * r + 2] >= N)
+            return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)Nsub);
+        int64_t *off = (int64_t *)malloc(sizeof(int64_t) * (size_t)Nsub);
+        if (!scores || !off) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t r = 0; r < n_rows; r++) {
+                int64_t b = rows[3 * r], hd = rows[3 * r + 1], n = rows[3 * r + 2];
+                int p, qq;
+                int64_t jq;
+                oracle_dst_index(pattern, s, T, H, W, n, &p, &qq, &jq);
+                for (int64_t j = 0; j < Nsub; j++)
+                    off[j] = (b * N + oracle_src_index(pattern, s, T, H, W, p, qq, j)) * C + hd * D;
+                attention_row(q, (b * N + n) * C + hd * D, k, v, off, Nsub, D, scale, dtype, scores, out + r * D);
+            }
+        }
+        free(scores);
+        free(off);
+    }
+    return fail ? -2 : 0;
+}
+
+/*
+ * Brute force for tiny grids (Sec. 3.1: a token interacts only with tokens of its own sub-figure):
+ * full N x N attention in the original order where the logit of a pair is -inf unless both tokens
+ * are in the same batch element and have the same (p,q) class.  Uses only the class of a token,
+ * never its position j, and never a permuted copy.
+ */
+int oracle_masked_dense_attention(const void *q, const void *k, const void *v, double *out, int B, int heads, int T, int H, int W,
+                                  int D, int s, int pattern, double scale, int dtype)
+{
+    if (!q || !k || !v || !out || heads < 1 || D < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W;
+    double *logit = (double *)malloc(sizeof(double) * (size_t)N);
+    if (!logit) return -2;
+    for (int64_t b = 0; b < B; b++)
+        for (int hd = 0; hd < heads; hd++)
+            for (int64_t n = 0; n < N; n++) {
+                int pn, qn, pm, qm;
+                int64_t jn, jm;
+                int64_t qo = (b * N + n) * C + (int64_t)hd * D;
+                oracle_dst_index(pattern, s, T, H, W, n, &pn, &qn, &jn);
+                double m = -INFINITY;
+                for (int64_t mm = 0; mm < N; mm++) {
+                    oracle_dst_index(pattern, s, T, H, W, mm, &pm, &qm, &jm);
+                    if (pm != pn || qm != qn) {
+                        logit[mm] = -INFINITY;
+                        continue;
+                    }
+                    int64_t ko = (b * N + mm) * C + (int64_t)hd * D;
+                    double acc = 0.0;
+                    for (int d = 0; d < D; d++) acc += load_elem(q, dtype, qo + d) * load_elem(k, dtype, ko + d);
+                    logit[mm] = scale * acc;
+                    if (logit[mm] > m) m = logit[mm];
+                }
+                double denom = 0.0;
+                for (int d = 0; d < D; d++) out[qo + d] = 0.0;
+                for (int64_t mm = 0; mm < N; mm++) {
+                    double pj = exp(logit[mm] - m); /* exp(-inf) = 0 for masked pairs */
+                    denom += pj;
+                    int64_t vo = (b * N + mm) * C + (int64_t)hd * D;
+                    for (int d = 0; d < D; d++) out[qo + d] += pj * load_elem(v, dtype, vo + d);
+                }
+                for (int d = 0; d < D; d++) out[qo + d] /= denom;
+            }
+    free(logit);
+    return 0;
+}
+
+int oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}
