@@ -1,0 +1,113 @@
+/*
+ * skiparse.h -- C ABI of the MI355X (gfx950) Skiparse-2D attention library.
+ *
+ * The library computes the forward pass of the sparse attention layer of OSP-Next (Sec. 3.1
+ * "Skiparse-2D Attention", Algorithm 1 "Skiparse Rearrange"): a (T,H,W) token grid is split into s*s
+ * spatially strided subsequences (token-wise or group-wise), ordinary softmax attention runs inside
+ * every subsequence, and the result is put back in the original token order.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned, and must stay alive
+ *     until `stream` has passed the call.  The library never allocates, frees or synchronises: a call
+ *     only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Original layout  x[b][n][head][d], n = (t*H + h)*W + w, contiguous      (Alg. 1: "b (t h w) c").
+ *   - Sparse layout    y[sb][j][head][d], sb = (p*s + q)*B + b, j = (t*(H/s) + hs)*(W/s) + ws
+ *                      (Alg. 1: "(p q b) (t h w) c", batch fastest inside sb).
+ *       token-wise: h = hs*s + p,                 w = ws*s + q                    (Alg. 1, orig_to_tsa)
+ *       group-wise: h = (hs/s)*s*s + p*s + hs%s,  w = (ws/s)*s*s + q*s + ws%s     (Alg. 1, orig_to_gsa)
+ *   - Shape rules: token-wise needs H % s == 0 and W % s == 0; group-wise needs H % (s*s) == 0 and
+ *     W % (s*s) == 0 (Sec. 3.2: the smallest repeatable unit is s^2 x s^2).  s = 1 is legal: the permute is
+ *     a copy and sparse attention equals full attention.
+ *   - Return value: SKIPARSE_OK or a negative error code.  Arguments are validated before the first HIP
+ *     call, so a bad call touches no memory and launches nothing.
+ */
+#ifndef SKIPARSE_H
+#define SKIPARSE_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SKIPARSE_TOKEN = 0, SKIPARSE_GROUP = 1 };                       /* pattern */
+enum { SKIPARSE_BF16 = 0, SKIPARSE_FP32 = 1, SKIPARSE_FP8_E4M3 = 2 };  /* element type of a tensor */
+enum { SKIPARSE_FUSED = 1u };                                          /* flags of skiparse_attn_fwd */
+
+enum {
+    SKIPARSE_OK = 0,
+    SKIPARSE_EINVAL = -1,       /* null pointer, non-positive size, unknown enum, src == dst, misaligned pointer */
+    SKIPARSE_ESHAPE = -2,       /* H or W not divisible as the pattern requires, or sizes overflow 31-bit row counts */
+    SKIPARSE_EUNSUPPORTED = -3, /* no kernel for this head_dim / element type */
+    SKIPARSE_EWORKSPACE = -4,   /* workspace missing or smaller than skiparse_workspace_bytes() */
+    SKIPARSE_EHIP = -5          /* a kernel launch failed; see skiparse_last_hip_error() */
+};
+
+/*
+ * Rearrangement original -> sparse (Alg. 1, orig_to_tsa / orig_to_gsa): dst[sb][j][:] = src[b][n(sb,j)][:].
+ * Rows of heads*head_dim elements are moved verbatim (bit-exact) for any element type.
+ * src: [B][T*H*W][heads][head_dim]; dst: [s*s*B][T*H*W/(s*s)][heads][head_dim]; src and dst must not overlap.
+ */
+int skiparse_permute(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                     int dtype, void* stream);
+
+/* Inverse rearrangement sparse -> original (Alg. 1, tsa_to_orig / gsa_to_orig): dst[b][n(sb,j)][:] = src[sb][j][:]. */
+int skiparse_unpermute(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                       int dtype, void* stream);
+
+/*
+ * Full attention (the dense blocks of the hybrid model, Sec. 3.4; also the per-subsequence step of Sec. 3.1):
+ * for every (b, head):  out = softmax(q k^T * scale) v  over all N = T*H*W tokens, no mask, no dropout.
+ * q, k, v, out: [B][N][heads][head_dim] bf16 (only N = T*H*W matters).  scale <= 0 selects 1/sqrt(head_dim).
+ * dtype must be SKIPARSE_BF16; head_dim 64 or 128.  Accumulation and softmax are fp32, probabilities are
+ * rounded to bf16 for the second matrix product, the output is rounded to bf16 (round to nearest even).
+ */
+int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
+                   int head_dim, float scale, int dtype, void* stream);
+
+/*
+ * Skiparse-2D attention (Sec. 3.1): out = unpermute(attention(permute(q), permute(k), permute(v))).
+ * q, k, v, out are all in the ORIGINAL layout [B][T*H*W][heads][head_dim] bf16.
+ *   flags = 0              three permutes, attention on the s*s*B subsequences, one unpermute.  Needs a
+ *                          workspace of skiparse_workspace_bytes() bytes (four permuted tensors).
+ *   flags = SKIPARSE_FUSED one kernel that computes each row's address from (subsequence, position); no
+ *                          permuted copy is written and no workspace is needed (workspace may be NULL).
+ * Both give the same result up to fp32 summation order.
+ */
+int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
+                      int head_dim, int s, int pattern, float scale, int dtype, unsigned flags, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Bytes of device workspace skiparse_attn_fwd needs for these arguments (0 for the fused path, 0 on bad arguments). */
+size_t skiparse_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int dtype, unsigned flags);
+
+/*
+ * 8-bit variant (motivated by Sec. 3.5, which runs the attention MatMuls in an 8-bit format; here OCP fp8 e4m3
+ * with fine-grained scales instead of per-tensor HiF8).
+ * skiparse_quantize_fp8: x (bf16, ORIGINAL layout) -> x8 (e4m3fn bytes, SPARSE layout) and
+ * scales[sb][head][ceil(Nsub/128)] (fp32) with scale = max|x| over a block of 128 consecutive tokens of one
+ * subsequence and head (all head_dim channels), divided by 448; an all-zero block gets scale 1.  x8 = rne(x/scale),
+ * saturating.
+ */
+int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
+                          int s, int pattern, void* stream);
+
+/*
+ * Attention on the quantised, already permuted tensors; out_bf16 is written in the ORIGINAL layout.
+ * S = (q8 k8^T) * sq * sk * scale; probabilities are multiplied by the key block's V scale and rounded to e4m3
+ * for the second matrix product, which accumulates in fp32.
+ */
+int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* sq, const float* sk, const float* sv,
+                          void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                          float scale, void* stream);
+
+/* Text for an error code; never NULL. */
+const char* skiparse_strerror(int code);
+
+/* The hipError_t (as int) of the last failed launch on this thread, 0 if none. */
+int skiparse_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKIPARSE_H */

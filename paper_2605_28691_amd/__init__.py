@@ -1,0 +1,151 @@
+"""MI355X-native Skiparse-2D attention: thin Python binding over the C ABI in ``include/skiparse.h``.
+
+Argument marshalling only.  Tensors are ``torch`` CUDA(HIP) tensors used purely as device memory; every step of
+the path runs in the library's own kernels on the current torch stream.  There is no CPU fallback: without the
+built library, or on a bad argument, a call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libskiparse.so")
+
+TOKEN, GROUP = 0, 1
+BF16, FP32, FP8_E4M3 = 0, 1, 2
+FUSED = 1
+PATTERNS = {"token": TOKEN, "group": GROUP}
+_DTYPES = {torch.bfloat16: BF16, torch.float32: FP32, torch.uint8: FP8_E4M3, torch.float8_e4m3fn: FP8_E4M3}
+
+_lib = None
+
+
+class SkiparseError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        msg = lib().skiparse_strerror(code).decode()
+        extra = f" [hipError {lib().skiparse_last_hip_error()}]" if code == -5 else ""
+        super().__init__(f"{what}: {msg} (code {code}){extra}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libskiparse.so (built by ``paper_2605_28691_amd.build.build()``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it first (python -m paper_2605_28691_amd.build); there is no fallback path"
+            )
+        L = ctypes.CDLL(_LIB_PATH)
+        i, vp, f, u, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_uint, ctypes.c_size_t
+        L.skiparse_permute.restype = i
+        L.skiparse_permute.argtypes = [vp, vp] + [i] * 9 + [vp]
+        L.skiparse_unpermute.restype = i
+        L.skiparse_unpermute.argtypes = [vp, vp] + [i] * 9 + [vp]
+        L.dense_attn_fwd.restype = i
+        L.dense_attn_fwd.argtypes = [vp] * 4 + [i] * 6 + [f, i, vp]
+        L.skiparse_attn_fwd.restype = i
+        L.skiparse_attn_fwd.argtypes = [vp] * 4 + [i] * 8 + [f, i, u, vp, sz, vp]
+        L.skiparse_workspace_bytes.restype = sz
+        L.skiparse_workspace_bytes.argtypes = [i] * 8 + [u]
+        L.skiparse_quantize_fp8.restype = i
+        L.skiparse_quantize_fp8.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
+        L.skiparse_attn_fwd_fp8.restype = i
+        L.skiparse_attn_fwd_fp8.argtypes = [vp] * 7 + [i] * 8 + [f, vp]
+        L.skiparse_strerror.restype = ctypes.c_char_p
+        L.skiparse_strerror.argtypes = [i]
+        L.skiparse_last_hip_error.restype = i
+        L.skiparse_last_hip_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, name: str) -> ctypes.c_void_p:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _check(code: int, what: str) -> None:
+    if code != 0:
+        raise SkiparseError(code, what)
+
+
+def _dims(x: torch.Tensor, T: int, H: int, W: int):
+    B, N, heads, D = x.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    return B, heads, D
+
+
+def skiparse_permute(x: torch.Tensor, T: int, H: int, W: int, s: int, pattern: str, out: torch.Tensor | None = None):
+    """[B][N][heads][D] -> [s*s*B][N/s^2][heads][D] (original -> sparse layout), bit-exact row gather."""
+    B, heads, D = _dims(x, T, H, W)
+    if out is None:
+        out = torch.empty((s * s * B, (T * H * W) // (s * s), heads, D), dtype=x.dtype, device=x.device)
+    _check(
+        lib().skiparse_permute(_dev(x, "x"), _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[pattern], _DTYPES[x.dtype], _stream()),
+        "skiparse_permute",
+    )
+    return out
+
+
+def skiparse_unpermute(y: torch.Tensor, T: int, H: int, W: int, s: int, pattern: str, out: torch.Tensor | None = None):
+    """[s*s*B][N/s^2][heads][D] -> [B][N][heads][D] (sparse -> original layout)."""
+    SB, Nsub, heads, D = y.shape
+    B = SB // (s * s)
+    if SB != B * s * s or Nsub * s * s != T * H * W:
+        raise ValueError("sparse-layout shape does not match the grid")
+    if out is None:
+        out = torch.empty((B, T * H * W, heads, D), dtype=y.dtype, device=y.device)
+    _check(
+        lib().skiparse_unpermute(_dev(y, "y"), _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[pattern], _DTYPES[y.dtype], _stream()),
+        "skiparse_unpermute",
+    )
+    return out
+
+
+def dense_attn_fwd(q, k, v, T: int, H: int, W: int, scale: float = 0.0, out: torch.Tensor | None = None):
+    """softmax(q k^T * scale) v over all T*H*W tokens for every (batch, head); bf16 in, bf16 out."""
+    B, heads, D = _dims(q, T, H, W)
+    if out is None:
+        out = torch.empty_like(q)
+    _check(
+        lib().dense_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), B, heads, T, H, W, D, float(scale),
+                             _DTYPES[q.dtype], _stream()),
+        "dense_attn_fwd",
+    )
+    return out
+
+
+def skiparse_workspace_bytes(B, heads, T, H, W, D, s, fused: bool) -> int:
+    return int(lib().skiparse_workspace_bytes(B, heads, T, H, W, D, s, BF16, FUSED if fused else 0))
+
+
+def skiparse_attn_fwd(q, k, v, T: int, H: int, W: int, s: int, pattern: str, scale: float = 0.0, fused: bool = True,
+                      out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """Skiparse-2D attention, q/k/v/out in the original layout.  The unfused path needs a uint8 device workspace of
+    skiparse_workspace_bytes() bytes; one is allocated with torch if none is passed."""
+    B, heads, D = _dims(q, T, H, W)
+    if out is None:
+        out = torch.empty_like(q)
+    ws_ptr, ws_bytes = ctypes.c_void_p(0), 0
+    if not fused:
+        need = skiparse_workspace_bytes(B, heads, T, H, W, D, s, False)
+        if workspace is None:
+            workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+        ws_ptr, ws_bytes = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    _check(
+        lib().skiparse_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), B, heads, T, H, W, D, s,
+                                PATTERNS[pattern], float(scale), _DTYPES[q.dtype], FUSED if fused else 0, ws_ptr, ws_bytes,
+                                _stream()),
+        "skiparse_attn_fwd",
+    )
+    return out

@@ -1,0 +1,233 @@
+// C ABI of the library: argument validation and dispatch.  Everything is checked before the first HIP call, so the
+// error paths run on a host without a GPU.
+#include "../../include/skiparse.h"
+
+#include <stdint.h>
+
+#include "kernels.h"
+
+using namespace skiparse;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int elem_size(int dtype) {
+    switch (dtype) {
+        case SKIPARSE_BF16: return 2;
+        case SKIPARSE_FP32: return 4;
+        case SKIPARSE_FP8_E4M3: return 1;
+        default: return 0;
+    }
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// [a, a + a_bytes) and [b, b + b_bytes) share at least one byte
+bool overlap2(const void* a, size_t a_bytes, const void* b, size_t b_bytes) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + b_bytes && y < x + a_bytes;
+}
+bool overlap(const void* a, const void* b, size_t bytes) { return overlap2(a, bytes, b, bytes); }
+
+struct Shape {
+    size_t n_tok;     // T*H*W
+    size_t n_sub;     // n_tok / s^2
+    size_t row_elems; // heads*head_dim
+    size_t elems;     // B*n_tok*row_elems
+};
+
+// Checks everything that does not involve pointers.  Returns SKIPARSE_OK and fills `sh`, or an error code.
+int check_shape(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, Shape* sh) {
+    if (B < 1 || heads < 1 || T < 1 || H < 1 || W < 1 || head_dim < 1 || s < 1) return SKIPARSE_EINVAL;
+    if (pattern != SKIPARSE_TOKEN && pattern != SKIPARSE_GROUP) return SKIPARSE_EINVAL;
+    if (s > 1024) return SKIPARSE_ESHAPE;
+    const int unit = pattern == SKIPARSE_TOKEN ? s : s * s;
+    if (H % unit != 0 || W % unit != 0) return SKIPARSE_ESHAPE;
+    const uint64_t n_tok = (uint64_t)T * (uint64_t)H * (uint64_t)W;
+    const uint64_t rows = n_tok * (uint64_t)B;
+    if (rows >= (1ull << 31)) return SKIPARSE_ESHAPE;  // row numbers are 32-bit in the kernels
+    const uint64_t n_sub = n_tok / ((uint64_t)s * s);
+    if (n_sub * (uint64_t)(W / s) >= (1ull << 32)) return SKIPARSE_ESHAPE;  // range of the multiply-high division
+    const uint64_t row_elems = (uint64_t)heads * (uint64_t)head_dim;
+    if (row_elems >= (1ull << 31) || rows * row_elems >= (1ull << 40)) return SKIPARSE_ESHAPE;
+    sh->n_tok = (size_t)n_tok;
+    sh->n_sub = (size_t)n_sub;
+    sh->row_elems = (size_t)row_elems;
+    sh->elems = (size_t)(rows * row_elems);
+    return SKIPARSE_OK;
+}
+
+GridMap make_gridmap(int T, int H, int W, int s, int pattern) {
+    GridMap g;
+    const int n_tok = T * H * W;
+    g.mode = s == 1 ? MODE_DENSE : (pattern == SKIPARSE_TOKEN ? MODE_TOKEN : MODE_GROUP);
+    g.s = s;
+    g.W = W;
+    g.n_tok = n_tok;
+    g.n_sub = n_tok / (s * s);
+    g.ws = make_fastdiv((uint32_t)(W / s));
+    g.sdiv = make_fastdiv((uint32_t)s);
+    return g;
+}
+
+GridMap make_dense_gridmap(size_t n) {
+    GridMap g;
+    g.mode = MODE_DENSE;
+    g.s = 1;
+    g.W = 1;
+    g.n_tok = (int)n;
+    g.n_sub = (int)n;
+    g.ws = make_fastdiv(1);
+    g.sdiv = make_fastdiv(1);
+    return g;
+}
+
+int finish(hipError_t e) {
+    if (e == hipSuccess) return SKIPARSE_OK;
+    g_last_hip_error = (int)e;
+    return SKIPARSE_EHIP;
+}
+
+int permute_common(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                   int dtype, void* stream, int to_sparse) {
+    if (!src || !dst) return SKIPARSE_EINVAL;
+    const int esz = elem_size(dtype);
+    if (esz == 0) return SKIPARSE_EINVAL;
+    Shape sh;
+    const int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (misaligned(src) || misaligned(dst)) return SKIPARSE_EINVAL;
+    const size_t row_bytes = sh.row_elems * (size_t)esz;
+    if (row_bytes % 16 != 0) return SKIPARSE_EUNSUPPORTED;
+    if (overlap(src, dst, sh.elems * (size_t)esz)) return SKIPARSE_EINVAL;
+    const GridMap g = make_gridmap(T, H, W, s, pattern);
+    return finish(launch_permute(src, dst, B, g, row_bytes, to_sparse, (hipStream_t)stream));
+}
+
+int check_attn_ptrs(const void* q, const void* k, const void* v, const void* out, size_t bytes) {
+    if (!q || !k || !v || !out) return SKIPARSE_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out)) return SKIPARSE_EINVAL;
+    if (overlap(out, q, bytes) || overlap(out, k, bytes) || overlap(out, v, bytes)) return SKIPARSE_EINVAL;
+    return SKIPARSE_OK;
+}
+
+size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+}  // namespace
+
+extern "C" {
+
+int skiparse_permute(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                     int dtype, void* stream) {
+    return permute_common(src, dst, B, heads, T, H, W, head_dim, s, pattern, dtype, stream, 1);
+}
+
+int skiparse_unpermute(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                       int dtype, void* stream) {
+    return permute_common(src, dst, B, heads, T, H, W, head_dim, s, pattern, dtype, stream, 0);
+}
+
+int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
+                   int head_dim, float scale, int dtype, void* stream) {
+    Shape sh;
+    int rc = check_shape(B, heads, T, H, W, head_dim, 1, SKIPARSE_TOKEN, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
+    if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
+    rc = check_attn_ptrs(q, k, v, out, sh.elems * 2);
+    if (rc != SKIPARSE_OK) return rc;
+    AttnArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = out;
+    a.B = B; a.heads = heads; a.head_dim = head_dim;
+    a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+    a.g = make_dense_gridmap(sh.n_tok);
+    return finish(launch_attn_bf16(a, (hipStream_t)stream));
+}
+
+size_t skiparse_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int dtype, unsigned flags) {
+    Shape sh;
+    if (check_shape(B, heads, T, H, W, head_dim, s, SKIPARSE_TOKEN, &sh) != SKIPARSE_OK) return 0;
+    if (dtype != SKIPARSE_BF16 || (flags & SKIPARSE_FUSED)) return 0;
+    return 4 * align256(sh.elems * 2);
+}
+
+int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
+                      int head_dim, int s, int pattern, float scale, int dtype, unsigned flags, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    Shape sh;
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (elem_size(dtype) == 0 || (flags & ~(unsigned)SKIPARSE_FUSED)) return SKIPARSE_EINVAL;
+    if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
+    const size_t bytes = sh.elems * 2;
+    rc = check_attn_ptrs(q, k, v, out, bytes);
+    if (rc != SKIPARSE_OK) return rc;
+    AttnArgs a;
+    a.B = B; a.heads = heads; a.head_dim = head_dim;
+    a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+    hipStream_t st = (hipStream_t)stream;
+    if (flags & SKIPARSE_FUSED) {
+        a.q = q; a.k = k; a.v = v; a.out = out;
+        a.g = make_gridmap(T, H, W, s, pattern);
+        return finish(launch_attn_bf16(a, st));
+    }
+    const size_t need = 4 * align256(bytes);
+    if (!workspace || workspace_bytes < need || misaligned(workspace)) return SKIPARSE_EWORKSPACE;
+    if (overlap2(workspace, need, q, bytes) || overlap2(workspace, need, k, bytes) || overlap2(workspace, need, v, bytes) ||
+        overlap2(workspace, need, out, bytes))
+        return SKIPARSE_EINVAL;
+    char* w = (char*)workspace;
+    void* qp = w;
+    void* kp = w + align256(bytes);
+    void* vp = w + 2 * align256(bytes);
+    void* op = w + 3 * align256(bytes);
+    const GridMap g = make_gridmap(T, H, W, s, pattern);
+    const size_t row_bytes = sh.row_elems * 2;
+    hipError_t e;
+    if ((e = launch_permute(q, qp, B, g, row_bytes, 1, st)) != hipSuccess) return finish(e);
+    if ((e = launch_permute(k, kp, B, g, row_bytes, 1, st)) != hipSuccess) return finish(e);
+    if ((e = launch_permute(v, vp, B, g, row_bytes, 1, st)) != hipSuccess) return finish(e);
+    a.q = qp; a.k = kp; a.v = vp; a.out = op;
+    a.B = B * s * s;  // the subsequences are the batch of the inner attention (Alg. 1: "(p q b)")
+    a.g = make_dense_gridmap(sh.n_sub);
+    if ((e = launch_attn_bf16(a, st)) != hipSuccess) return finish(e);
+    return finish(launch_permute(op, out, B, g, row_bytes, 0, st));
+}
+
+int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
+                          int s, int pattern, void* stream) {
+    (void)stream;
+    Shape sh;
+    const int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (!x_bf16 || !x8 || !scales) return SKIPARSE_EINVAL;
+    return SKIPARSE_EUNSUPPORTED;
+}
+
+int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* sq, const float* sk, const float* sv,
+                          void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                          float scale, void* stream) {
+    (void)stream; (void)scale;
+    Shape sh;
+    const int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (!q8 || !k8 || !v8 || !sq || !sk || !sv || !out_bf16) return SKIPARSE_EINVAL;
+    return SKIPARSE_EUNSUPPORTED;
+}
+
+const char* skiparse_strerror(int code) {
+    switch (code) {
+        case SKIPARSE_OK: return "ok";
+        case SKIPARSE_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, unknown enum, overlapping buffers)";
+        case SKIPARSE_ESHAPE: return "grid not divisible as the pattern requires, or sizes out of range";
+        case SKIPARSE_EUNSUPPORTED: return "no kernel for this head_dim / element type";
+        case SKIPARSE_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case SKIPARSE_EHIP: return "kernel launch failed (see skiparse_last_hip_error)";
+        default: return "unknown error code";
+    }
+}
+
+int skiparse_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

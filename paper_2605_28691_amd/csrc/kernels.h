@@ -1,0 +1,32 @@
+// Host-side launchers of the HIP kernels; every function only enqueues work on `stream` and returns the
+// hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "index_map.h"
+
+namespace skiparse {
+
+// Row gather/scatter between the original and the sparse layout.  `to_sparse` != 0: dst is sparse.
+hipError_t launch_permute(const void* src, void* dst, int B, const GridMap& g, size_t row_bytes, int to_sparse,
+                          hipStream_t stream);
+
+// Flash-attention forward, bf16.  Units are (batch-like index, head); with g.mode == MODE_DENSE the batch-like
+// index is a batch element of n_sub tokens, otherwise it is a subsequence (p, q, b) addressed inside the
+// original layout through src_token().
+struct AttnArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* out;
+    int B;          // batch elements of the original layout
+    int heads;
+    int head_dim;
+    float scale;    // multiplies the logits
+    GridMap g;
+};
+hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace skiparse

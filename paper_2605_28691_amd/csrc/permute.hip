@@ -1,0 +1,54 @@
+// Row gather/scatter between the original and the sparse token order (Algorithm 1, orig_to_tsa / orig_to_gsa and
+// their inverses).  Bound by HBM bandwidth: every row of heads*head_dim elements is contiguous in both layouts, so
+// one wavefront moves one row with 16-byte accesses per lane (1 KiB contiguous per wavefront instruction) and the
+// index arithmetic is done once per row.
+#include "kernels.h"
+
+namespace skiparse {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int PERMUTE_WAVES = 4;  // rows per workgroup
+
+template <int UNROLL>
+__global__ __launch_bounds__(PERMUTE_WAVES * 64) void permute_rows_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                                          int B, GridMap g, uint32_t chunks_per_row,
+                                                                          uint32_t n_rows, int to_sparse) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t row = blockIdx.x * PERMUTE_WAVES + (threadIdx.x >> 6);  // row number in the sparse layout
+    if (row >= n_rows) return;
+    // sparse row -> (sb, j) -> (p, q, b) -> row number in the original layout
+    const uint32_t n_sub = (uint32_t)g.n_sub;
+    const uint32_t sb = row / n_sub, j = row - sb * n_sub;
+    const uint32_t pq = sb / (uint32_t)B, b = sb - pq * (uint32_t)B;
+    const uint32_t p = pq / (uint32_t)g.s, q = pq - p * (uint32_t)g.s;
+    const uint32_t orig_row = b * (uint32_t)g.n_tok + src_token(g, p, q, j);
+    const u32x4* s = src + (size_t)(to_sparse ? orig_row : row) * chunks_per_row;
+    u32x4* d = dst + (size_t)(to_sparse ? row : orig_row) * chunks_per_row;
+    uint32_t c = lane;
+    for (; c + (UNROLL - 1) * 64u < chunks_per_row; c += UNROLL * 64u) {
+        u32x4 tmp[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; u++) tmp[u] = __builtin_nontemporal_load(s + c + u * 64u);
+#pragma unroll
+        for (int u = 0; u < UNROLL; u++) __builtin_nontemporal_store(tmp[u], d + c + u * 64u);
+    }
+    for (; c < chunks_per_row; c += 64u) __builtin_nontemporal_store(__builtin_nontemporal_load(s + c), d + c);
+}
+
+hipError_t launch_permute(const void* src, void* dst, int B, const GridMap& g, size_t row_bytes, int to_sparse,
+                          hipStream_t stream) {
+    const uint32_t chunks = (uint32_t)(row_bytes / 16);
+    const uint32_t s2 = g.mode == MODE_DENSE ? 1u : (uint32_t)(g.s * g.s);
+    const uint32_t n_rows = (uint32_t)B * s2 * (uint32_t)g.n_sub;
+    const uint32_t blocks = (n_rows + PERMUTE_WAVES - 1) / PERMUTE_WAVES;
+    if (chunks >= 5 * 64)
+        permute_rows_kernel<5><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+    else if (chunks >= 3 * 64)
+        permute_rows_kernel<3><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+    else
+        permute_rows_kernel<1><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+    return hipGetLastError();
+}
+
+}  // namespace skiparse

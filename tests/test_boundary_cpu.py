@@ -1,0 +1,98 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol, and rejects
+bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "skiparse.h")
+LIBPATH = os.path.join(ROOT, "paper_2605_28691_amd", "libskiparse.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_28691_amd as sk
+
+    if not os.path.exists(LIBPATH):
+        from paper_2605_28691_amd import build
+
+        build.build()
+    return sk.lib()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
+            "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror(lib):
+    for code in range(-6, 1):
+        assert lib.skiparse_strerror(code)
+
+
+FAKE = 0x10000  # a non-null, 16-byte aligned address; never dereferenced because validation fails first
+
+
+def test_permute_rejects_bad_arguments(lib):
+    p, q = ctypes.c_void_p(FAKE), ctypes.c_void_p(FAKE + (1 << 30))
+    ok_args = [1, 2, 2, 8, 8, 64, 2, 0, 0]
+
+    def call(src, dst, *a):
+        return lib.skiparse_permute(src, dst, *a, None)
+
+    assert call(None, q, *ok_args) == -1
+    assert call(p, None, *ok_args) == -1
+    assert call(p, p, *ok_args) == -1  # src == dst
+    assert call(p, ctypes.c_void_p(FAKE + 64), *ok_args) == -1  # overlapping
+    assert call(ctypes.c_void_p(FAKE + 4), q, *ok_args) == -1  # misaligned
+    assert call(p, q, 0, 2, 2, 8, 8, 64, 2, 0, 0) == -1  # B = 0
+    assert call(p, q, 1, 2, 2, 8, 8, 64, 0, 0, 0) == -1  # s = 0
+    assert call(p, q, 1, 2, 2, 8, 8, 64, 2, 7, 0) == -1  # unknown pattern
+    assert call(p, q, 1, 2, 2, 8, 8, 64, 2, 0, 9) == -1  # unknown dtype
+    assert call(p, q, 1, 2, 2, 6, 8, 64, 2, 1, 0) == -2  # group-wise needs H % 4 == 0
+    assert call(p, q, 1, 2, 2, 7, 8, 64, 2, 0, 0) == -2  # token-wise needs H % 2 == 0
+    assert call(p, q, 1, 2, 1 << 12, 1 << 10, 1 << 10, 64, 2, 0, 0) == -2  # 2^32 tokens
+    assert call(p, q, 1, 1, 2, 8, 8, 3, 2, 0, 2) == -3  # 3-byte rows cannot be moved in 16-byte pieces
+    assert lib.skiparse_unpermute(p, q, 1, 2, 2, 6, 8, 64, 2, 1, 0, None) == -2
+
+
+def test_attention_rejects_bad_arguments(lib):
+    a = [ctypes.c_void_p(FAKE + i * (1 << 30)) for i in range(5)]
+    f = ctypes.c_float(0.0)
+    assert lib.dense_attn_fwd(None, a[1], a[2], a[3], 1, 2, 2, 8, 8, 64, f, 0, None) == -1
+    assert lib.dense_attn_fwd(a[0], a[1], a[2], a[0], 1, 2, 2, 8, 8, 64, f, 0, None) == -1  # out aliases q
+    assert lib.dense_attn_fwd(a[0], a[1], a[2], a[3], 1, 2, 2, 8, 8, 96, f, 0, None) == -3  # head_dim 96
+    assert lib.dense_attn_fwd(a[0], a[1], a[2], a[3], 1, 2, 2, 8, 8, 64, f, 1, None) == -3  # fp32 attention
+    assert lib.dense_attn_fwd(a[0], a[1], a[2], a[3], 1, 2, 2, 8, 8, 64, f, 5, None) == -1  # unknown dtype
+
+    def sparse(flags, ws, ws_bytes, H=8, pattern=0, s=2):
+        return lib.skiparse_attn_fwd(a[0], a[1], a[2], a[3], 1, 2, 2, H, 8, 64, s, pattern, f, 0, flags, ws, ws_bytes, None)
+
+    assert sparse(1, None, 0, H=6, pattern=1) == -2
+    assert sparse(2, None, 0) == -1  # unknown flag bit
+    assert sparse(0, None, 0) == -4  # unfused path without a workspace
+    need = lib.skiparse_workspace_bytes(1, 2, 2, 8, 8, 64, 2, 0, 0)
+    assert need == 4 * 1 * 128 * 2 * 64 * 2
+    assert sparse(0, a[4], need - 1) == -4
+    assert lib.skiparse_workspace_bytes(1, 2, 2, 8, 8, 64, 2, 0, 1) == 0  # fused needs none
+    assert lib.skiparse_workspace_bytes(1, 2, 2, 7, 8, 64, 2, 0, 0) == 0  # bad shape
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    import paper_2605_28691_amd as sk
+
+    monkeypatch.setattr(sk, "_lib", None)
+    monkeypatch.setattr(sk, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        sk.lib()
