@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the Skiparse-2D attention hot path on one MI355X.
+
+One step = one fused skiparse_attn_fwd call (token-wise, s=2) on the 768P-shaped workload: B=1, 40 heads,
+head_dim 128, grid 21x48x80 (80,640 tokens; 160 attention units of 20,160 tokens).  Inputs are synthetic bf16
+N(0,1) tensors already resident in HBM.  Prints ONE JSON line.  Besides the headline it times the group-wise
+call, the unfused path (3 permutes + attention + unpermute), the library's dense attention on the same q,k,v
+(speed-up) and the permute alone (HBM GB/s), and it times the float64 oracle on a bounded sample of query rows
+on the host cores, using those rows as a parity check of the timed configuration.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+# Paper context only (end-to-end model speed-ups on other hardware; Tab. 2): not comparable to a kernel figure.
+PAPER_CONTEXT = {"e2e_speedup_h200_bf16": 1.64, "e2e_speedup_ascend950pr_hif8_720p": 1.69, "e2e_speedup_ascend950pr_hif8_768p": 2.27}
+
+
+def time_calls(fn, iters, warmup):
+    """Average milliseconds per call, measured with events on the stream the kernels are launched on."""
+    import torch
+
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="768p", choices=["480p", "768p"])
+    ap.add_argument("--cpu-rows", type=int, default=16384, help="query rows the oracle computes for cpu_baseline")
+    ap.add_argument("--skip-extras", action="store_true", help="only the headline timing (used under the profiler)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2605_28691_amd as sk
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    sk.lib()
+    w = si.WORKLOADS[args.workload]
+    t0 = time.time()
+    q, k, v = si.make_qkv(w)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    out = torch.empty_like(qd)
+    gen_s = time.time() - t0
+    T, H, W, s = w.T, w.H, w.W, w.s
+    flops = w.sparse_flops()
+
+    def fused(pattern):
+        return lambda: sk.skiparse_attn_fwd(qd, kd, vd, T, H, W, s, pattern, scale=w.scale, fused=True, out=out)
+
+    # ---- headline: W warm-up steps, then exactly K timed steps bracketed by synchronisation
+    for _ in range(args.warmup):
+        fused("token")()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        fused("token")()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - wall0) * 1e3 / args.steps
+    kernel_ms = ev0.elapsed_time(ev1) / args.steps  # one kernel per step: this is the kernel's average duration
+    ms = wall_ms
+    tflops = flops / (ms * 1e-3) / 1e12
+    result = {
+        "metric": "skiparse2d_attn_fwd_effective_tflops",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: B={w.B} heads={w.heads} head_dim={w.D} grid={T}x{H}x{W} ({w.N} tokens) s={s} token-wise, fused kernel",
+            "units": w.B * w.heads * s * s,
+            "tokens_per_subsequence": w.Nsub,
+            "flop_per_call": flops,
+            "seed": w.seed,
+        },
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {
+            "bound": "mfma",
+            "achieved": round(flops / (kernel_ms * 1e-3) / 1e12, 2),
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(flops / (kernel_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "traffic": None,
+            "kernel": "attn_fwd_bf16_kernel<128>",
+            "kernel_ms": round(kernel_ms, 4),
+        },
+        "paper_context": PAPER_CONTEXT,
+        "input_generation_s": round(gen_s, 1),
+    }
+
+    if not args.skip_extras:
+        extras = {}
+        it = max(3, min(10, args.steps))
+        if "group" in w.patterns:
+            g_ms = time_calls(fused("group"), it, 1)
+            extras["fused_group_ms"] = round(g_ms, 4)
+            extras["fused_group_tflops"] = round(flops / g_ms / 1e9, 2)
+        need = sk.skiparse_workspace_bytes(w.B, w.heads, T, H, W, w.D, s, False)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        u_ms = time_calls(lambda: sk.skiparse_attn_fwd(qd, kd, vd, T, H, W, s, "token", scale=w.scale, fused=False, out=out, workspace=ws), it, 1)
+        extras["unfused_token_ms"] = round(u_ms, 4)
+        yp = ws[: qd.numel() * 2].view(torch.bfloat16).view(s * s * w.B, w.Nsub, w.heads, w.D)
+        p_ms = time_calls(lambda: sk.skiparse_permute(qd, T, H, W, s, "token", out=yp), 10, 2)
+        up_ms = time_calls(lambda: sk.skiparse_unpermute(yp, T, H, W, s, "token", out=out), 10, 2)
+        tensor_bytes = qd.numel() * 2
+        extras["permute_ms"] = round(p_ms, 4)
+        extras["permute_GBps"] = round(2 * tensor_bytes / p_ms / 1e6, 1)
+        extras["unpermute_ms"] = round(up_ms, 4)
+        extras["unpermute_GBps"] = round(2 * tensor_bytes / up_ms / 1e6, 1)
+        extras["permute_frac_of_hbm_peak"] = round(2 * tensor_bytes / p_ms / 1e6 / PEAK_HBM_GBS, 4)
+        del ws, yp
+        d_ms = time_calls(lambda: sk.dense_attn_fwd(qd, kd, vd, T, H, W, scale=w.scale, out=out), 3, 1)
+        extras["dense_ms"] = round(d_ms, 4)
+        extras["dense_tflops"] = round(w.dense_flops() / d_ms / 1e9, 2)
+        extras["speedup_vs_dense"] = round(d_ms / ms, 3)
+        result["extras"] = extras
+
+        # ---- oracle on the host cores, on a bounded sample of query rows of the same workload; doubles as parity check
+        import oracle
+
+        fused("token")()
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(123)
+        rows = np.stack([rng.integers(0, w.B, args.cpu_rows), rng.integers(0, w.heads, args.cpu_rows), rng.integers(0, w.N, args.cpu_rows)], axis=1).astype(np.int64)
+        oq, ok_, ov = (si.as_oracle_array(t) for t in (q, k, v))
+        c0 = time.perf_counter()
+        want = oracle.skiparse_attention_rows(oq, ok_, ov, rows, T, H, W, s, "token", w.scale)
+        cpu_s = time.perf_counter() - c0
+        r = torch.from_numpy(rows).cuda()
+        got = out[r[:, 0], r[:, 2], r[:, 1]].cpu().to(torch.float64).numpy()
+        max_abs = float(np.abs(got - want).max())
+        rel_l2 = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+        row_flops = 4.0 * w.Nsub * w.D
+        result["cpu_baseline"] = {
+            "value": round(args.cpu_rows * row_flops / cpu_s / 1e12, 6),
+            "unit": "TFLOP/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{args.cpu_rows} of {w.B * w.heads * w.N} query rows drawn uniformly, each against all {w.Nsub} keys of its subsequence; {cpu_s:.1f} s",
+            "extrapolated_full_call_s": round(cpu_s * (w.B * w.heads * w.N) / args.cpu_rows, 1),
+        }
+        result["parity"] = {"rows": args.cpu_rows, "max_abs": max_abs, "rel_l2": rel_l2, "ok": bool(max_abs <= 2e-2 and rel_l2 <= 5e-3)}
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
