@@ -22,7 +22,7 @@ FLAGS = [
 
 def build(verbose: bool = False, save_temps: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS
+    cmd = [hipcc] + FLAGS + os.environ.get("SKIPARSE_EXTRA_FLAGS", "").split()
     if save_temps:
         tmp = os.path.join(HERE, "_build")
         os.makedirs(tmp, exist_ok=True)

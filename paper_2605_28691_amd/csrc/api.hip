@@ -48,7 +48,8 @@ int check_shape(int B, int heads, int T, int H, int W, int head_dim, int s, int 
     const uint64_t rows = n_tok * (uint64_t)B;
     if (rows >= (1ull << 31)) return SKIPARSE_ESHAPE;  // row numbers are 32-bit in the kernels
     const uint64_t n_sub = n_tok / ((uint64_t)s * s);
-    if (n_sub * (uint64_t)(W / s) >= (1ull << 32)) return SKIPARSE_ESHAPE;  // range of the multiply-high division
+    const uint64_t dmax = (uint64_t)(W / s) > (uint64_t)s ? (uint64_t)(W / s) : (uint64_t)s;
+    if (n_sub * dmax >= (1ull << 32)) return SKIPARSE_ESHAPE;  // range of the multiply-high divisions
     const uint64_t row_elems = (uint64_t)heads * (uint64_t)head_dim;
     if (row_elems >= (1ull << 31) || rows * row_elems >= (1ull << 40)) return SKIPARSE_ESHAPE;
     sh->n_tok = (size_t)n_tok;
@@ -58,28 +59,39 @@ int check_shape(int B, int heads, int T, int H, int W, int head_dim, int s, int 
     return SKIPARSE_OK;
 }
 
-GridMap make_gridmap(int T, int H, int W, int s, int pattern) {
-    GridMap g;
-    const int n_tok = T * H * W;
-    g.mode = s == 1 ? MODE_DENSE : (pattern == SKIPARSE_TOKEN ? MODE_TOKEN : MODE_GROUP);
-    g.s = s;
-    g.W = W;
-    g.n_tok = n_tok;
-    g.n_sub = n_tok / (s * s);
-    g.ws = make_fastdiv((uint32_t)(W / s));
-    g.sdiv = make_fastdiv((uint32_t)s);
-    return g;
-}
-
 GridMap make_dense_gridmap(size_t n) {
     GridMap g;
     g.mode = MODE_DENSE;
     g.s = 1;
-    g.W = 1;
+    g.W = 0;
     g.n_tok = (int)n;
     g.n_sub = (int)n;
-    g.ws = make_fastdiv(1);
+    g.a = 1;
+    g.b = 0;
+    g.cmul = 0;
+    g.ws = make_fastdiv(0xffffffffu);  // multiplier 2: the quotient is 0 for every position below 2^31
+    g.step_r = 0;
+    g.step_w = 64;
     g.sdiv = make_fastdiv(1);
+    return g;
+}
+
+GridMap make_gridmap(int T, int H, int W, int s, int pattern) {
+    const int n_tok = T * H * W;
+    if (s == 1) return make_dense_gridmap((size_t)n_tok);
+    GridMap g;
+    g.mode = pattern == SKIPARSE_TOKEN ? MODE_TOKEN : MODE_GROUP;
+    g.s = s;
+    g.W = W;
+    g.n_tok = n_tok;
+    g.n_sub = n_tok / (s * s);
+    g.a = pattern == SKIPARSE_TOKEN ? (uint32_t)s : 1u;
+    g.b = pattern == SKIPARSE_TOKEN ? 0u : (uint32_t)(s * s - s);
+    g.cmul = pattern == SKIPARSE_TOKEN ? 1u : (uint32_t)s;
+    g.ws = make_fastdiv((uint32_t)(W / s));
+    g.sdiv = make_fastdiv((uint32_t)s);
+    g.step_r = 64u / (uint32_t)(W / s);
+    g.step_w = 64u % (uint32_t)(W / s);
     return g;
 }
 
@@ -103,6 +115,16 @@ int permute_common(const void* src, void* dst, int B, int heads, int T, int H, i
     if (overlap(src, dst, sh.elems * (size_t)esz)) return SKIPARSE_EINVAL;
     const GridMap g = make_gridmap(T, H, W, s, pattern);
     return finish(launch_permute(src, dst, B, g, row_bytes, to_sparse, (hipStream_t)stream));
+}
+
+// The attention kernels address rows with 32-bit byte offsets inside one batch element and form them with 24-bit
+// multiplies: tokens per batch element, row length W and bytes per token row must stay below 2^24, and one batch
+// element below 4 GiB.
+int check_attn_ranges(const Shape& sh, int W, int elem_bytes) {
+    const uint64_t row_bytes = (uint64_t)sh.row_elems * (uint64_t)elem_bytes;
+    if (sh.n_tok >= (1u << 24) || (uint64_t)W >= (1u << 24) || row_bytes >= (1u << 24)) return SKIPARSE_ESHAPE;
+    if ((uint64_t)sh.n_tok * row_bytes >= (1ull << 32)) return SKIPARSE_ESHAPE;
+    return SKIPARSE_OK;
 }
 
 int check_attn_ptrs(const void* q, const void* k, const void* v, const void* out, size_t bytes) {
@@ -135,6 +157,8 @@ int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B
     if (rc != SKIPARSE_OK) return rc;
     if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
     if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
+    rc = check_attn_ranges(sh, W, 2);
+    if (rc != SKIPARSE_OK) return rc;
     rc = check_attn_ptrs(q, k, v, out, sh.elems * 2);
     if (rc != SKIPARSE_OK) return rc;
     AttnArgs a;
@@ -161,6 +185,8 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
     if (elem_size(dtype) == 0 || (flags & ~(unsigned)SKIPARSE_FUSED)) return SKIPARSE_EINVAL;
     if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
     const size_t bytes = sh.elems * 2;
+    rc = check_attn_ranges(sh, W, 2);
+    if (rc != SKIPARSE_OK) return rc;
     rc = check_attn_ptrs(q, k, v, out, bytes);
     if (rc != SKIPARSE_OK) return rc;
     AttnArgs a;

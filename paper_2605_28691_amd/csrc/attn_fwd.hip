@@ -2,52 +2,65 @@
 //
 // Computes, for every attention unit (a subsequence or batch element, and a head),
 //     O = softmax(Q K^T * scale) V                      (Sec. 3.1: attention inside each subsequence)
-// without ever forming the N x N matrix: keys are walked in tiles of 64 with a running row maximum and row sum.
+// without ever forming the N x N matrix: keys are walked in blocks of 32 with a running row maximum and row sum.
 //
 // Mapping onto the hardware
-//   * One workgroup = 4 wavefronts; each wavefront owns QT tiles of 32 query rows for the whole key walk.
+//   * One workgroup = 4 wavefronts; each wavefront owns 32 query rows for the whole key walk; two workgroups share a
+//     CU (<= 256 VGPRs, 74 KiB LDS each), so every SIMD interleaves two independent wavefronts.
 //   * The products are formed transposed, S^T = K Q^T and O^T = V^T P^T, with v_mfma_f32_32x32x16_bf16.  In the
 //     32x32 accumulator layout lane l holds column l%32, so every lane owns ONE query: its 16 registers per 32-key
 //     block are 16 keys of that query, the row maximum and sum are in-lane loops plus one exchange with lane l^32,
 //     and the exponentiated accumulator registers, rounded to bf16, ARE the B operand of the second product -- the
-//     probabilities never leave registers.
-//   * K and V tiles are staged through LDS (global -> registers -> LDS, double buffered, one barrier per tile).
-//     K is read back as the A operand with 16-byte reads; V^T is read with ds_read_b64_tr_b16, the gfx950
-//     transposing LDS read, so V stays row-major in LDS.
-//   * The key order inside a 16-key MFMA step is whatever the accumulator layout gives (keys 4h..4h+3 and
-//     8+4h..8+4h+3 for lane half h); V^T is fetched in the same order, so no shuffle is needed.
+//     probabilities never leave registers.  The key order inside a 16-key MFMA step is whatever the accumulator
+//     layout gives (keys 4h..4h+3 and 8+4h..8+4h+3 for lane half h); V^T is fetched in the same order.
+//   * Software pipeline over 32-key blocks: step b issues the MFMAs of  S(b+1) = K(b+1) Q^T  and  O += V(b-1)^T P(b-1)^T
+//     and does the softmax arithmetic of block b on the vector ALU.  The three are independent inside a step, so the
+//     matrix pipe and the vector ALU overlap within one wavefront as well as across the two on a SIMD.
+//   * In the steady state the instruction order of a step is written out by hand and fixed with scheduling fences:
+//     the PV MFMAs first, with the block maximum and the reference update between them, then the QK MFMAs with two
+//     pairs of exponentials between each, and every LDS fragment read two MFMAs before its use.
+//   * K and V tiles of 64 keys are staged global -> registers -> LDS, double buffered, K one tile ahead of V (a
+//     window of two steps reads K tile W and V tile W-1), one barrier per window; the global loads of a tile are issued
+//     a whole window before their LDS stores.  K is read back as the A operand
+//     with 16-byte reads (rows padded to D*2+16 bytes); V^T is read with ds_read_b64_tr_b16, the gfx950 transposing
+//     LDS read (rows padded to D*2+64 bytes), so V stays row-major in LDS.
+//   * Lazy rescale: the reference maximum of a row is raised only when it grew by more than 2^8 in some lane of the
+//     wavefront, so multiplying the O accumulators by the correction is a rare, separate block.  Numerator and
+//     denominator always use the same reference, so the result is exact up to rounding.
 //   * Row addresses come from src_token(): in the dense mode position j is row j, in the sparse modes it is the
 //     token the Skiparse rearrangement (Algorithm 1) would have put at position j, so q, k, v are read and out is
-//     written in the original layout and no permuted copy exists.
+//     written in the original layout and no permuted copy exists.  One thread stages one row per tile and advances its
+//     (row, column) position by 64 keys with adds and one wrap, so the index arithmetic is a handful of full-rate
+//     24-bit multiply-adds per thread per 64 keys.
 //   * Workgroups are numbered so that all query tiles of one unit run on the same XCD (workgroup id mod 8 selects
 //     the XCD under round-robin dispatch) and walk K/V in step: the per-XCD L2 then serves the re-reads.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace skiparse {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
-constexpr int KT = 64;          // keys per tile
+constexpr int KT = 64;          // keys per staged tile (two 32-key blocks)
 constexpr int NTHREADS = 256;   // 4 wavefronts
-constexpr float RESCALE_LOG2 = 8.0f;  // the running maximum is only raised when it grew by more than 2^8
+constexpr float RESCALE_LOG2 = 8.0f;  // the reference maximum is only raised when it grew by more than 2^8
 
 template <int D>
 struct Tile {
-    static constexpr int CHUNKS = D / 8;                 // 16-byte chunks per row
-    static constexpr int ROWS_PER_PASS = NTHREADS / CHUNKS;
-    static constexpr int PASSES = KT / ROWS_PER_PASS;
+    static constexpr int CH = D / 8;                     // 16-byte chunks per row
+    static constexpr int CPT = CH / 4;                   // chunks per thread: 4 threads stage one row
     static constexpr int K_STRIDE = D * 2 + 16;          // bytes; +16 spreads the 16-byte reads of 16 rows over all banks
     static constexpr int V_STRIDE = D * 2 + 64;          // bytes; +64 keeps the 4 rows of a transposing read on distinct banks
     static constexpr int K_BYTES = KT * K_STRIDE;
     static constexpr int V_BYTES = KT * V_STRIDE;
-    static constexpr int BUF_BYTES = K_BYTES + V_BYTES;
 };
 
 // Exchange between lanes l and l^32 (the two halves of one query's keys) with v_permlane32_swap: afterwards `lo` is
@@ -60,25 +73,29 @@ __device__ inline void lane_pair(float x, float& lo, float& hi) {
     lo = __uint_as_float(r0);
     hi = __uint_as_float(r1);
 }
-__device__ inline float lane_pair_max(float x) {
-    float lo, hi;
-    lane_pair(x, lo, hi);
-    return fmaxf(lo, hi);
+
+// a*b + c on 24-bit unsigned operands (full-rate, unlike the 32-bit multiplies); operand ranges are checked on the host
+__device__ inline uint32_t mad24(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
 }
-__device__ inline float lane_pair_sum(float x) {
-    float lo, hi;
-    lane_pair(x, lo, hi);
-    return lo + hi;
+// a value that is the same in every lane, moved to a scalar register
+__device__ inline uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ inline size_t uniform(size_t x) {
+    return ((size_t)uniform((uint32_t)(x >> 32)) << 32) | uniform((uint32_t)x);
 }
 
-template <int D, int QT>
-__global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles,
-                                                                                    uint32_t n_units) {
+// GROUP selects the group-wise index map (two extra divisions by s per staged row); token-wise and dense use GROUP = false.
+template <int D, int QT, bool GROUP>
+__global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
     using TL = Tile<D>;
-    constexpr int KS = D / 16;   // MFMA steps along head_dim for S^T = K Q^T
-    constexpr int MT = D / 32;   // 32-row blocks of O^T
-    constexpr int BR = 128 * QT; // query rows per workgroup
-    __shared__ __attribute__((aligned(16))) char lds[2 * TL::BUF_BYTES];
+    constexpr int KS = D / 16;     // MFMA steps along head_dim for S^T = K Q^T
+    constexpr int MT = D / 32;     // 32-row blocks of O^T
+    constexpr int BR = 128 * QT;   // query rows per workgroup: QT tiles of 32 per wavefront
+    __shared__ __attribute__((aligned(16))) char lds[2 * TL::K_BYTES + 2 * TL::V_BYTES];
+    char* const lds_k = lds;
+    char* const lds_v = lds + 2 * TL::K_BYTES;
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t lq = lane & 31u, h = lane >> 5;
@@ -89,16 +106,16 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
     const uint32_t unit = ul * 8u + xcd;
     if (unit >= n_units) return;
     const uint32_t bb = unit / (uint32_t)a.heads, head = unit - bb * (uint32_t)a.heads;
-    uint32_t p = 0, q = 0, b = bb;
+    uint32_t p = 0, q = 0, b0 = bb;
     if (a.g.mode != MODE_DENSE) {
         const uint32_t pq = bb / (uint32_t)a.B;
-        b = bb - pq * (uint32_t)a.B;
+        b0 = bb - pq * (uint32_t)a.B;
         p = pq / (uint32_t)a.g.s;
         q = pq - p * (uint32_t)a.g.s;
     }
     const uint32_t n_seq = (uint32_t)a.g.n_sub;
     const size_t C = (size_t)a.heads * D;
-    const size_t unit_off = (size_t)b * (uint32_t)a.g.n_tok * C + (size_t)head * D;  // elements
+    const size_t unit_off = uniform((size_t)b0 * (uint32_t)a.g.n_tok * C + (size_t)head * D);  // elements
     const __bf16* Qg = (const __bf16*)a.q + unit_off;
     const __bf16* Kg = (const __bf16*)a.k + unit_off;
     const __bf16* Vg = (const __bf16*)a.v + unit_off;
@@ -106,47 +123,79 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane = query lq, 8 consecutive channels starting at 16*ks + 8*h
     bf16x8 qf[QT][KS];
-    size_t q_row_off[QT];
     bool q_valid[QT];
+    size_t q_row_off[QT];
 #pragma unroll
     for (int qi = 0; qi < QT; qi++) {
-        const uint32_t j = qt * BR + (wave * QT + qi) * 32u + lq;
-        q_valid[qi] = j < n_seq;
-        q_row_off[qi] = (size_t)src_token(a.g, p, q, q_valid[qi] ? j : n_seq - 1u) * C;
+        const uint32_t jq = qt * BR + (wave * QT + qi) * 32u + lq;
+        q_valid[qi] = jq < n_seq;
+        q_row_off[qi] = (size_t)src_token(a.g, p, q, q_valid[qi] ? jq : n_seq - 1u) * C;
 #pragma unroll
-        for (int ks = 0; ks < KS; ks++)
-            qf[qi][ks] = *(const bf16x8*)(Qg + q_row_off[qi] + ks * 16 + 8 * h);
+        for (int ks = 0; ks < KS; ks++) qf[qi][ks] = *(const bf16x8*)(Qg + q_row_off[qi] + ks * 16 + 8 * h);
     }
 
-    // ---- staging: thread -> (row r0 + pass*ROWS_PER_PASS, 16-byte chunk c) of a K/V tile
-    const uint32_t st_c = tid % TL::CHUNKS, st_r = tid / TL::CHUNKS;
-    u32x4 kreg[TL::PASSES], vreg[TL::PASSES];
-    auto load_tile = [&](uint32_t t) {
-#pragma unroll
-        for (int ps = 0; ps < TL::PASSES; ps++) {
-            uint32_t j = t * KT + st_r + ps * TL::ROWS_PER_PASS;
-            j = j < n_seq ? j : n_seq - 1u;  // rows past the end are masked later; read a valid row instead
-            const size_t off = (size_t)src_token(a.g, p, q, j) * C + st_c * 8;
-            kreg[ps] = *(const u32x4*)(Kg + off);
-            vreg[ps] = *(const u32x4*)(Vg + off);
+    // ---- staging: 4 threads per row of a 64-key tile.  K chunks of a thread are contiguous (st_piece*CPT + i), V chunks
+    // are interleaved (st_piece + 4*i): with the two row paddings each choice makes the 16-byte LDS stores conflict free.
+    const uint32_t st_row = tid >> 2, st_piece = tid & 3u;
+    u32x4 kreg[TL::CPT], vreg[TL::CPT];  // staging registers: loaded during one window, stored to LDS at the start of the next
+    // Byte offset of this thread's row of a tile, relative to the unit's base (fits 32 bits: checked on the host).
+    // Tiles are visited in order, so (r, ws) = (j / Ws, j % Ws) of the row are advanced by 64 positions with adds and one
+    // wrap instead of being divided out again; the products use 24-bit multiplies (operands checked on the host).
+    const uint32_t Ws = a.g.ws.d, row_bytes = (uint32_t)C * 2u;
+    const uint32_t last_off = src_token(a.g, p, q, n_seq - 1u) * row_bytes;  // rows past the end read the last valid row
+    uint32_t st_r = a.g.ws.div(st_row), st_ws = st_row - st_r * Ws;  // position of tile 0's row (st_row < 64 <= any range limit)
+    uint32_t st_j = st_row;
+    const uint32_t row_c = p * a.g.cmul, col_c = q * a.g.cmul;
+    auto row_off_now = [&]() -> uint32_t {
+        uint32_t row = mad24(st_r, a.g.a, row_c);
+        uint32_t w = mad24(st_ws, a.g.a, col_c);
+        if (GROUP) {
+            row = mad24(a.g.sdiv.div(st_r), a.g.b, row);
+            w = mad24(a.g.sdiv.div(st_ws), a.g.b, w);
         }
+        const uint32_t off = mad24(mad24(row, (uint32_t)a.g.W, w), row_bytes, 0u);
+        return st_j < n_seq ? off : last_off;
     };
-    auto store_tile = [&](uint32_t buf) {
-        char* base = lds + buf * TL::BUF_BYTES;
+    auto advance_tile = [&]() {
+        st_j += KT;
+        st_r += a.g.step_r;
+        st_ws += a.g.step_w;
+        const bool wrap = st_ws >= Ws;
+        st_ws = wrap ? st_ws - Ws : st_ws;
+        st_r = wrap ? st_r + 1u : st_r;
+    };
+    auto tile_row_off_next = [&]() -> uint32_t {  // offset of the next tile's row; call once per tile, in order
+        advance_tile();
+        return row_off_now();
+    };
+    auto load_k = [&](uint32_t off) {
 #pragma unroll
-        for (int ps = 0; ps < TL::PASSES; ps++) {
-            const uint32_t r = st_r + ps * TL::ROWS_PER_PASS;
-            *(u32x4*)(base + r * TL::K_STRIDE + st_c * 16) = kreg[ps];
-            *(u32x4*)(base + TL::K_BYTES + r * TL::V_STRIDE + st_c * 16) = vreg[ps];
-        }
+        for (int i = 0; i < TL::CPT; i++)
+            kreg[i] = *(const u32x4*)((const char*)Kg + off + (st_piece * TL::CPT + i) * 16);
+    };
+    auto load_v = [&](uint32_t off) {
+#pragma unroll
+        for (int i = 0; i < TL::CPT; i++) vreg[i] = *(const u32x4*)((const char*)Vg + off + (st_piece + 4 * i) * 16);
+    };
+    auto store_k = [&](uint32_t buf) {
+#pragma unroll
+        for (int i = 0; i < TL::CPT; i++)
+            *(u32x4*)(lds_k + buf * TL::K_BYTES + st_row * TL::K_STRIDE + (st_piece * TL::CPT + i) * 16) = kreg[i];
+    };
+    auto store_v = [&](uint32_t buf) {
+#pragma unroll
+        for (int i = 0; i < TL::CPT; i++)
+            *(u32x4*)(lds_v + buf * TL::V_BYTES + st_row * TL::V_STRIDE + (st_piece + 4 * i) * 16) = vreg[i];
     };
 
-    // ---- running state: every lane tracks its own query (pairs l, l^32 hold the same values)
+    // ---- running state: every lane tracks its own query (lanes l and l^32 hold the same m_ref; l_run is a partial sum)
     f32x16 oacc[QT][MT];
-    float m_run[QT], l_run[QT];
+    f32x16 sreg[2][QT];     // S(b) lives in sreg[b & 1]
+    bf16x8 preg[2][QT][2];  // P(b) lives in preg[b & 1][query tile][16-key half]
+    float m_ref[QT], l_run[QT];
 #pragma unroll
     for (int qi = 0; qi < QT; qi++) {
-        m_run[qi] = -INFINITY;
+        m_ref[qi] = -INFINITY;
         l_run[qi] = 0.f;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
@@ -156,115 +205,259 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
     const float c = a.scale * 1.4426950408889634f;  // logits are kept raw; exp(x*scale) = exp2(x*c)
 
     // LDS read offsets that do not depend on the tile
-    const uint32_t k_rd = lq * TL::K_STRIDE + h * 16;  // + kt*32*K_STRIDE + ks*32
-    // transposing V read: 16-lane group covers 4 keys x 16 channels; lane i of the group addresses key i/4, channels 4*(i%4)..
+    const uint32_t k_rd = lq * TL::K_STRIDE + h * 16;  // + half*32*K_STRIDE + ks*32
+    // transposing V read: a 16-lane group covers 4 keys x 16 channels; lane i of the group addresses key i/4, channels 4*(i%4)..
     const uint32_t li = lane & 15u, lgrp = (lane >> 4) & 1u;
-    const uint32_t v_rd = (4 * h + (li >> 2)) * TL::V_STRIDE + (lgrp * 16 + 4 * (li & 3u)) * 2;  // + g16*16*V_STRIDE (+8 rows) + mt*64
+    const uint32_t v_rd = (4 * h + (li >> 2)) * TL::V_STRIDE + (lgrp * 16 + 4 * (li & 3u)) * 2;  // + (half*32 + m2*16 (+8))*V_STRIDE + mt*64
 
-    const uint32_t n_kt = (n_seq + KT - 1) / KT;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (uint32_t t = 0; t < n_kt; t++) {
-        const bool more = t + 1 < n_kt;
-        if (more) load_tile(t + 1);
-        const char* kb = lds + (t & 1u) * TL::BUF_BYTES;
-        const char* vb = kb + TL::K_BYTES;
-
-        // S^T = K Q^T for two blocks of 32 keys
-        f32x16 sacc[QT][2];
+    // S(block) = K(block) Q^T from K tile buffer kb, 32-key half `half`; each K fragment feeds all QT query tiles
+    auto qk = [&](const char* kb, int half, f32x16 (&s)[QT]) {
+        f32x16 acc[QT];
 #pragma unroll
         for (int qi = 0; qi < QT; qi++)
 #pragma unroll
-            for (int kt = 0; kt < 2; kt++)
+            for (int r = 0; r < 16; r++) acc[qi][r] = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; r++) sacc[qi][kt][r] = 0.f;
+        for (int ks = 0; ks < KS; ks++) {
+            const bf16x8 kf = *(const bf16x8*)(kb + k_rd + half * 32 * TL::K_STRIDE + ks * 32);
 #pragma unroll
-        for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-                const bf16x8 kf = *(const bf16x8*)(kb + k_rd + kt * 32 * TL::K_STRIDE + ks * 32);
-#pragma unroll
-                for (int qi = 0; qi < QT; qi++)
-                    sacc[qi][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qi][ks], sacc[qi][kt], 0, 0, 0);
+            for (int qi = 0; qi < QT; qi++) {
+                acc[qi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qi][ks], acc[qi], 0, 0, 0);
             }
-
-        // keys past the end of the sequence (last tile only) get a logit of -inf
-        if (!more && (n_seq % KT) != 0) {
-#pragma unroll
-            for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const uint32_t key = t * KT + kt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if (key >= n_seq) {
-#pragma unroll
-                        for (int qi = 0; qi < QT; qi++) sacc[qi][kt][r] = -INFINITY;
-                    }
-                }
         }
-
-        // online softmax; probabilities become the B operand of O^T += V^T P^T
-        bf16x8 pf[QT][4];
 #pragma unroll
-        for (int qi = 0; qi < QT; qi++) {
-            float mx = sacc[qi][0][0];
+        for (int qi = 0; qi < QT; qi++) s[qi] = acc[qi];
+    };
+    // O^T += V(block)^T P(block)^T from V tile buffer vb, 32-key half `half`
+    auto pv = [&](const char* vb, int half, const bf16x8 (&pf)[QT][2]) {
 #pragma unroll
-            for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) mx = fmaxf(mx, sacc[qi][kt][r]);
-            mx = lane_pair_max(mx);
-            const float m_cand = fmaxf(m_run[qi], mx);
-            const bool grow = (m_cand - m_run[qi]) * c > RESCALE_LOG2;
-            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                const float alpha = __builtin_amdgcn_exp2f((m_run[qi] - m_cand) * c);
-                l_run[qi] *= alpha;
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) oacc[qi][mt][r] *= alpha;
-                m_run[qi] = m_cand;
-            }
-            const float mc = m_run[qi] * c;
-            float lsum = 0.f;
-#pragma unroll
-            for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-                for (int g = 0; g < 2; g++) {
-                    bf16x8 pk;
-#pragma unroll
-                    for (int e = 0; e < 8; e++) {
-                        const float pe = __builtin_amdgcn_exp2f(fmaf(sacc[qi][kt][g * 8 + e], c, -mc));
-                        lsum += pe;
-                        pk[e] = (__bf16)pe;
-                    }
-                    pf[qi][kt * 2 + g] = pk;
-                }
-            l_run[qi] += lsum;
-        }
-
-        // O^T += V^T P^T: 4 steps of 16 keys, MT blocks of 32 channels
-#pragma unroll
-        for (int g16 = 0; g16 < 4; g16++)
+        for (int m2 = 0; m2 < 2; m2++)
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
-                const char* va = vb + v_rd + g16 * 16 * TL::V_STRIDE + mt * 64;
+                const char* va = vb + v_rd + (half * 32 + m2 * 16) * TL::V_STRIDE + mt * 64;
                 const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))va);
                 const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + 8 * TL::V_STRIDE));
                 const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                 for (int qi = 0; qi < QT; qi++)
-                    oacc[qi][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qi][g16], oacc[qi][mt], 0, 0, 0);
+                    oacc[qi][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qi][m2], oacc[qi][mt], 0, 0, 0);
             }
+    };
+    auto max3 = [](float x, float y, float z) { return fmaxf(fmaxf(x, y), z); };
+    // exponentials of one block against the reference mc (= m_ref * c): bf16 probabilities and their fp32 sum
+    auto exps = [&](const f32x16& s, float mc, bf16x8 (&pf)[2]) -> float {
+        float lsum = 0.f;
+#pragma unroll
+        for (int g = 0; g < 2; g++) {
+            bf16x8 pk;
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[g * 8 + e], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s[g * 8 + e + 1], c, -mc))};
+                const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
+                // the row sum is taken over the rounded probabilities, the same values the second product uses
+                lsum = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum, false);
+                pk[e] = pb[0];
+                pk[e + 1] = pb[1];
+            }
+            pf[g] = pk;
+        }
+        return lsum;
+    };
+    // One pipeline step for block b = 2W-1 (PAR = 1) or 2W (PAR = 0) of window W: K tile W in kb, V tile W-1 in vb.
+    //   QK(b+1) -> sreg[PAR^1]   softmax(b): sreg[PAR] -> preg[PAR]   PV(b-1) with preg[PAR^1]
+    // Generic form, used for the first and last windows (optional QK / PV, key masking); instruction order is left to
+    // the compiler.  The steady-state windows use step_manual below.
+    auto step = [&](auto DO_QK, auto DO_PV, auto MASK, auto PARC, uint32_t blk, const char* kb, const char* vb) {
+        constexpr int PAR = decltype(PARC)::value;
+        if (decltype(DO_QK)::value) qk(kb, PAR ^ 1, sreg[PAR ^ 1]);
+        float lsum[QT], m_new[QT];
+        bool grow[QT];
+        unsigned long long grow_mask = 0;
+#pragma unroll
+        for (int qi = 0; qi < QT; qi++) {
+            f32x16& s = sreg[PAR][qi];
+            if (decltype(MASK)::value) {
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const uint32_t key = blk * 32u + 8 * (r >> 2) + 4 * h + (r & 3);
+                    s[r] = key < n_seq ? s[r] : -INFINITY;
+                }
+            }
+            const float mx = fmaxf(max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8])),
+                                   max3(max3(s[9], s[10], s[11]), max3(s[12], s[13], s[14]), s[15]));
+            float lo, hi;
+            lane_pair(mx, lo, hi);
+            m_new[qi] = max3(m_ref[qi], lo, hi);
+            grow[qi] = (m_new[qi] - m_ref[qi]) * c > RESCALE_LOG2;  // same in lanes l and l^32
+            grow_mask |= __builtin_amdgcn_ballot_w64(grow[qi]);
+            const float m_use = grow[qi] ? m_new[qi] : m_ref[qi];
+            m_new[qi] = __builtin_amdgcn_exp2f((m_ref[qi] - m_use) * c);  // alpha: 1 where the reference stays, 0 on the first block
+            m_ref[qi] = m_use;
+            l_run[qi] = fmaf(l_run[qi], m_new[qi], exps(s, m_use * c, preg[PAR][qi]));
+        }
+        if (decltype(DO_PV)::value) pv(vb, PAR ^ 1, preg[PAR ^ 1]);
+        // The probabilities are only consumed by the next step; pin them here so that their computation stays in
+        // this step's block (next to the MFMAs it overlaps with) instead of sinking below the branch.
+#pragma unroll
+        for (int qi = 0; qi < QT; qi++) asm volatile("" ::"v"(preg[PAR][qi][0]), "v"(preg[PAR][qi][1]));
+        if (__builtin_expect(grow_mask != 0, 0)) {
+#pragma unroll
+            for (int qi = 0; qi < QT; qi++) {
+                const float alpha = m_new[qi];
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) oacc[qi][mt][r] *= alpha;  // after PV(b-1), before PV(b)
+            }
+        }
+    };
+    // Hand-ordered version of a full, unmasked step (QT = 1): the instruction order is fixed group by group with scheduling
+    // fences.  PV(b-1) MFMAs run first while the vector ALU finds the block maximum and settles the reference; the QK(b+1)
+    // MFMAs follow while the exponentials are taken, two pairs per MFMA.  LDS fragments are read two MFMAs ahead.
+    auto step_manual = [&](auto PARC, const char* kb, const char* vb) {
+        static_assert(QT == 1, "manual schedule is written for one query tile per wavefront");
+        constexpr int PAR = decltype(PARC)::value;
+        constexpr int NPV = 2 * MT, NQK = KS;
+        f32x16& s = sreg[PAR][0];
+        const bf16x8(&pp)[2] = preg[PAR ^ 1][0];
+        auto read_v = [&](int i) -> bf16x8 {  // fragment of PV MFMA i: 16-key group m2 = i / MT, channel block mt = i % MT
+            const char* va = vb + v_rd + ((PAR ^ 1) * 32 + (i / MT) * 16) * TL::V_STRIDE + (i % MT) * 64;
+            const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))va);
+            const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + 8 * TL::V_STRIDE));
+            return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        };
+        auto read_k = [&](int ks) -> bf16x8 { return *(const bf16x8*)(kb + k_rd + (PAR ^ 1) * 32 * TL::K_STRIDE + ks * 32); };
+        bf16x8 fr[NPV + NQK];  // every fragment has its own name; lifetimes are short, so few registers are live at a time
+        fr[0] = read_v(0);
+        fr[1] = read_v(1);
+        __builtin_amdgcn_sched_barrier(0);
+        // --- phase 1: PV MFMAs; maximum of the block and the new reference
+        float t0, t1, t2, t3, t4, mx = 0.f, lo = 0.f, hi = 0.f, m_new = 0.f, alpha = 1.f, mc = 0.f;
+        bool grow = false;
+#pragma unroll
+        for (int i = 0; i < NPV; i++) {
+            if (i + 2 < NPV) fr[i + 2] = read_v(i + 2);
+            else fr[i + 2] = read_k(i + 2 - NPV);
+            oacc[0][i % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i], pp[i / MT], oacc[0][i % MT], 0, 0, 0);
+            const int slot = i * 8 / NPV;  // spread the 8 chain slots over the PV MFMAs
+            const int slot_end = (i + 1) * 8 / NPV;
+#pragma unroll
+            for (int c8 = slot; c8 < slot_end; c8++) {
+                if (c8 == 0) { t0 = max3(s[0], s[1], s[2]); t1 = max3(s[3], s[4], s[5]); t2 = max3(s[6], s[7], s[8]); }
+                if (c8 == 1) { t3 = max3(s[9], s[10], s[11]); t4 = max3(s[12], s[13], s[14]); t0 = max3(t0, t1, t2); }
+                if (c8 == 2) { mx = fmaxf(max3(t3, t4, s[15]), t0); }
+                if (c8 == 3) { lane_pair(mx, lo, hi); }
+                if (c8 == 4) { m_new = max3(m_ref[0], lo, hi); grow = (m_new - m_ref[0]) * c > RESCALE_LOG2; }
+                if (c8 == 5) {
+                    const float m_use = grow ? m_new : m_ref[0];
+                    alpha = __builtin_amdgcn_exp2f((m_ref[0] - m_use) * c);
+                    m_ref[0] = m_use;
+                    mc = m_use * c;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // --- phase 2: QK MFMAs; exponentials, 16 / NQK per MFMA
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[r] = 0.f;
+        float lsum = 0.f;
+        bf16x8 pk[2];
+#pragma unroll
+        for (int i = 0; i < NQK; i++) {
+            if (i + 2 < NQK) fr[NPV + i + 2] = read_k(i + 2);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[NPV + i], qf[0][i], acc, 0, 0, 0);
+#pragma unroll
+            for (int e = i * 16 / NQK; e < (i + 1) * 16 / NQK; e += 2) {
+                const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, -mc))};
+                const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
+                lsum = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum, false);
+                pk[e / 8][e % 8] = pb[0];
+                pk[e / 8][e % 8 + 1] = pb[1];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        sreg[PAR ^ 1][0] = acc;
+        preg[PAR][0][0] = pk[0];
+        preg[PAR][0][1] = pk[1];
+        l_run[0] = fmaf(l_run[0], alpha, lsum);
+        asm volatile("" ::"v"(preg[PAR][0][0]), "v"(preg[PAR][0][1]));
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) oacc[0][mt][r] *= alpha;
+        }
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
 
-        if (more) store_tile((t + 1) & 1u);
+    const uint32_t n_tiles = (n_seq + KT - 1) / KT;
+
+    // Staging schedule.  Window W reads K tile W and V tile W-1 from LDS.  At its start it stores the registers that were
+    // loaded during window W-1 (K tile W+1 -> K buffer (W+1)&1, V tile W -> V buffer W&1; neither buffer is read in window
+    // W) and then issues the loads of K tile W+2 and V tile W+1, which have a whole window to arrive.
+    // ---- prologue: K tile 0 to LDS; K tile 1 and V tile 0 into registers
+    uint32_t off_k = row_off_now();  // tile 0
+    load_k(off_k);
+    load_v(off_k);
+    store_k(0);
+    uint32_t off_v = tile_row_off_next();  // tile 1 (clamped to the last row if it does not exist)
+    load_k(off_v);
+    __syncthreads();
+
+    // ---- window 0: QK(0), then step 0 without PV
+    {
+        store_k(1);
+        store_v(0);
+        off_k = tile_row_off_next();  // tile 2
+        load_k(off_k);
+        load_v(off_v);                // tile 1
+        off_v = off_k;
+        qk(lds_k, 0, sreg[0]);
+        step(T_{}, F_{}, T_{}, P0{}, 0u, lds_k, lds_v);
         __syncthreads();
+    }
+    // ---- windows 1 .. n_tiles-2: all keys valid
+    uint32_t W = 1;
+    for (; W + 1 < n_tiles; W++) {
+        const char* kb = lds_k + (W & 1u) * TL::K_BYTES;
+        const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
+        store_k((W + 1u) & 1u);       // K tile W+1
+        store_v(W & 1u);              // V tile W
+        off_k = tile_row_off_next();  // tile W+2
+        load_k(off_k);
+        load_v(off_v);                // tile W+1
+        off_v = off_k;
+        step_manual(P1{}, kb, vb);
+        step_manual(P0{}, kb, vb);
+        __syncthreads();
+    }
+    // ---- window n_tiles-1 (if there is more than one tile): the last K tile, may hold keys past the end
+    if (W < n_tiles) {
+        const char* kb = lds_k + (W & 1u) * TL::K_BYTES;
+        const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
+        store_v(W & 1u);  // V tile W, the last one
+        step(T_{}, T_{}, T_{}, P1{}, 2 * W - 1, kb, vb);
+        step(T_{}, T_{}, T_{}, P0{}, 2 * W, kb, vb);
+        __syncthreads();
+        W++;
+    }
+    // ---- final window (W == n_tiles): softmax of the last block, the last two PVs
+    {
+        const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
+        step(F_{}, T_{}, T_{}, P1{}, 2 * W - 1, nullptr, vb);
+        pv(vb, 1, preg[1]);
     }
 
     // ---- epilogue: O = O^T / l, rounded to bf16; lane owns query lq, register r of block mt is channel 32*mt + 8*(r/4) + 4*h + r%4
 #pragma unroll
     for (int qi = 0; qi < QT; qi++) {
-        const float inv = 1.0f / lane_pair_sum(l_run[qi]);
+        float llo, lhi;
+        lane_pair(l_run[qi], llo, lhi);
+        const float inv = 1.0f / (llo + lhi);
         if (q_valid[qi]) {
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
@@ -279,21 +472,22 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
     }
 }
 
-template <int D, int QT>
+template <int D, int QT, bool GROUP>
 static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
-    const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 128 * QT - 1) / (128 * QT);
+    const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 128u * QT - 1u) / (128u * QT);
     const uint32_t units_padded = (n_units + 7u) / 8u * 8u;
     const uint64_t blocks = (uint64_t)units_padded * q_tiles;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    attn_fwd_bf16_kernel<D, QT><<<(uint32_t)blocks, NTHREADS, 0, stream>>>(a, q_tiles, n_units);
+    attn_fwd_bf16_kernel<D, QT, GROUP><<<(uint32_t)blocks, NTHREADS, 0, stream>>>(a, q_tiles, n_units);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
-    if (a.head_dim == 128) return launch_t<128, 1>(a, stream);
-    if (a.head_dim == 64) return launch_t<64, 1>(a, stream);
+    const bool group = a.g.b != 0;
+    if (a.head_dim == 128) return group ? launch_t<128, 1, true>(a, stream) : launch_t<128, 1, false>(a, stream);
+    if (a.head_dim == 64) return group ? launch_t<64, 1, true>(a, stream) : launch_t<64, 1, false>(a, stream);
     return hipErrorInvalidValue;
 }
 

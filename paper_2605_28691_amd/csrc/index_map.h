@@ -7,6 +7,9 @@
 //     r = j / Ws (= t*Hs + hs),  ws = j % Ws
 //     token-wise: t*H + h = r*s + p                      w = ws*s + q
 //     group-wise: t*H + h = (r/s)*s*s + p*s + r%s        w = (ws/s)*s*s + q*s + ws%s     (needs Hs % s == 0)
+// Both are instances of one branch-free form  f(x) = x*a + (x/s)*b + c  with (a, b) = (s, 0) for token-wise and
+// (1, s*s - s) for group-wise, c = p (or q) for token-wise and p*s (or q*s) for group-wise.  The dense case (position j is
+// token j) uses a = 1, b = 0, c = 0 and a divisor of 2^31 so that r is always 0.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -17,14 +20,16 @@ enum Mode : int { MODE_DENSE = 0, MODE_TOKEN = 1, MODE_GROUP = 2 };
 
 // Division of a 32-bit n by a run-time constant d through one multiply-high; exact while n * d < 2^32
 // (mul = floor(2^32 / d) + 1, so mul * d = 2^32 + e with 1 <= e <= d and the error term n * e / 2^32 stays below 1).
+// d = 1 would need a multiplier of 2^32: it is expressed as mul = 0 plus `one` = 1 (quotient = n * one).
 struct FastDiv {
     uint32_t d;
     uint32_t mul;
+    uint32_t one;
     __host__ __device__ inline uint32_t div(uint32_t n) const {
 #if defined(__HIP_DEVICE_COMPILE__)
-        return d == 1u ? n : __umulhi(n, mul);
+        return __umulhi(n, mul) + n * one;
 #else
-        return d == 1u ? n : (uint32_t)(((uint64_t)n * mul) >> 32);
+        return (uint32_t)(((uint64_t)n * mul) >> 32) + n * one;
 #endif
     }
 };
@@ -33,33 +38,30 @@ inline FastDiv make_fastdiv(uint32_t d) {
     FastDiv f;
     f.d = d;
     f.mul = d <= 1u ? 0u : (uint32_t)((1ull << 32) / d) + 1u;
+    f.one = d <= 1u ? 1u : 0u;
     return f;
 }
 
 struct GridMap {
-    int mode;     // MODE_DENSE: position j is token j
-    int s;        // sparse ratio
-    int W;        // original row length
-    int n_tok;    // tokens per batch element in the original layout (T*H*W)
-    int n_sub;    // tokens per subsequence
-    FastDiv ws;   // division by W/s
-    FastDiv sdiv; // division by s
+    int mode;      // MODE_DENSE: position j is token j
+    int s;         // sparse ratio
+    int W;         // original row length
+    int n_tok;     // tokens per batch element in the original layout (T*H*W)
+    int n_sub;     // tokens per subsequence
+    uint32_t a;    // f(x) = x*a + (x/s)*b + c, see above
+    uint32_t b;
+    uint32_t cmul; // c = p*cmul (rows) or q*cmul (columns)
+    FastDiv ws;    // division by W/s
+    uint32_t step_r;  // 64 / (W/s) and 64 % (W/s): how (j / Ws, j % Ws) move when j advances by one 64-key tile
+    uint32_t step_w;
+    FastDiv sdiv;  // division by s
 };
 
-__device__ inline uint32_t src_token(const GridMap& g, uint32_t p, uint32_t q, uint32_t j) {
-    if (g.mode == MODE_DENSE) return j;
-    uint32_t r = g.ws.div(j);
-    uint32_t ws = j - r * g.ws.d;
-    uint32_t row, w;
-    uint32_t s = (uint32_t)g.s;
-    if (g.mode == MODE_TOKEN) {
-        row = r * s + p;
-        w = ws * s + q;
-    } else {
-        uint32_t ro = g.sdiv.div(r), wo = g.sdiv.div(ws);
-        row = ro * s * s + p * s + (r - ro * s);
-        w = wo * s * s + q * s + (ws - wo * s);
-    }
+__host__ __device__ inline uint32_t src_token(const GridMap& g, uint32_t p, uint32_t q, uint32_t j) {
+    const uint32_t r = g.ws.div(j);
+    const uint32_t ws = j - r * g.ws.d;
+    const uint32_t row = r * g.a + g.sdiv.div(r) * g.b + p * g.cmul;
+    const uint32_t w = ws * g.a + g.sdiv.div(ws) * g.b + q * g.cmul;
     return row * (uint32_t)g.W + w;
 }
 
