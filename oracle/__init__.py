@@ -58,6 +58,12 @@ def _load():
         lib.oracle_skiparse_attention_rows.argtypes = [vp, vp, vp, vp, i64, vp, i, i, i, i, i, i, i, i, dbl, i]
         lib.oracle_masked_dense_attention.restype = i
         lib.oracle_masked_dense_attention.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, dbl, i]
+        lib.oracle_quantize_fp8.restype = i
+        lib.oracle_quantize_fp8.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, i]
+        lib.oracle_e4m3_encode.restype = ctypes.c_uint8
+        lib.oracle_e4m3_encode.argtypes = [ctypes.c_float]
+        lib.oracle_e4m3_decode.restype = dbl
+        lib.oracle_e4m3_decode.argtypes = [ctypes.c_uint8]
         lib.oracle_num_threads.restype = i
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -182,3 +188,34 @@ def masked_dense_attention(q, k, v, T: int, H: int, W: int, s: int, pattern: str
         "masked_dense_attention",
     )
     return out
+
+
+def e4m3_encode(y: float) -> int:
+    """E4M3 code of a float with |y| <= 448 (round to nearest even)."""
+    return int(_load().oracle_e4m3_encode(float(y)))
+
+
+def e4m3_decode(code: int) -> float:
+    return float(_load().oracle_e4m3_decode(int(code)))
+
+
+def e4m3_decode_array(codes: np.ndarray) -> np.ndarray:
+    """Values of an array of E4M3 codes as float64 (through the 256-entry decode table)."""
+    table = np.array([e4m3_decode(c) for c in range(256)], dtype=np.float64)
+    table[[0x7F, 0xFF]] = np.nan
+    return table[codes]
+
+
+def quantize_fp8(x: np.ndarray, T: int, H: int, W: int, s: int, pattern: str):
+    """bf16 bit patterns in the original layout -> (E4M3 codes in the sparse layout, float32 scales per
+    (subsequence, head, 128-position block)); the 8-bit workload's recipe."""
+    if x.dtype != np.uint16 or not x.flags.c_contiguous:
+        raise ValueError("quantize_fp8 takes C-contiguous uint16 bf16 bit patterns")
+    B, N, heads, D = x.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    nsub = N // (s * s)
+    x8 = np.empty((s * s * B, nsub, heads, D), dtype=np.uint8)
+    scales = np.empty((s * s * B, heads, (nsub + 127) // 128), dtype=np.float32)
+    _check(_load().oracle_quantize_fp8(_ptr(x), _ptr(x8), _ptr(scales), B, heads, T, H, W, D, s, PATTERNS[pattern]), "quantize_fp8")
+    return x8, scales

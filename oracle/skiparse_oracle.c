@@ -316,6 +316,87 @@ int oracle_masked_dense_attention(const void *q, const void *k, const void *v, d
     return 0;
 }
 
+/*
+ * 8-bit variant (the workload's recipe; the paper's own 8-bit format, HiF8 of Sec. 3.5, is proprietary and is replaced by
+ * OCP FP8 E4M3 with fine-grained scales).
+ *
+ * E4M3 ("fn" flavour: 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities, largest finite value 448 =
+ * 1.75 * 2^8, smallest subnormal 2^-9).  Encodes a float that already satisfies |y| <= 448, round to nearest, ties to even,
+ * written from the format definition.
+ */
+static uint8_t e4m3_encode(float y)
+{
+    uint8_t sign = (uint8_t)(signbit(y) ? 0x80 : 0x00);
+    double a = fabs((double)y);
+    if (a < 0.015625) { /* below the smallest normal 2^-6: multiples of 2^-9 */
+        double q = nearbyint(a * 512.0); /* default rounding mode: to nearest, ties to even; q in 0..8 */
+        return (uint8_t)(sign | (uint8_t)q); /* q == 8 is the code of 2^-6 (exponent field 1, mantissa 0) */
+    }
+    int e;
+    double f = frexp(a, &e); /* a = f * 2^e, f in [0.5, 1) */
+    e -= 1;                  /* a = (2f) * 2^e with 2f in [1, 2) */
+    double q = nearbyint((2.0 * f - 1.0) * 8.0); /* mantissa in eighths, 0..8 */
+    if (q == 8.0) {
+        q = 0.0;
+        e += 1;
+    }
+    return (uint8_t)(sign | (uint8_t)((e + 7) << 3) | (uint8_t)q);
+}
+
+double oracle_e4m3_decode(uint8_t code)
+{
+    int ef = (code >> 3) & 15, m = code & 7;
+    double v = ef == 0 ? m / 512.0 : ldexp(1.0 + m / 8.0, ef - 7);
+    return (code & 0x80) ? -v : v;
+}
+
+uint8_t oracle_e4m3_encode(float y) { return e4m3_encode(y); }
+
+/*
+ * Quantise x (bf16 bit patterns, ORIGINAL layout [B][N][heads][D]) to E4M3 codes in the SPARSE layout
+ * [s*s*B][Nsub][heads][D] with one float32 scale per (subsequence, head, block of 128 consecutive positions):
+ *   amax  = max |x| over the block (all D channels);  scale = amax / 448, inv = 448 / amax  (both float32; 1 if amax = 0)
+ *   code  = e4m3( clamp( x * inv, -448, 448 ) )        with x * inv rounded to float32 first
+ * scales is [s*s*B][heads][ceil(Nsub/128)].  The decision "which code" is taken in float32 on both sides.
+ */
+int oracle_quantize_fp8(const uint16_t *x, uint8_t *x8, float *scales, int B, int heads, int T, int H, int W, int D, int s,
+                        int pattern)
+{
+    if (!x || !x8 || !scales || heads < 1 || D < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W, Nsub = N / (s * s), nblk = (Nsub + 127) / 128;
+    for (int p = 0; p < s; p++)
+        for (int q = 0; q < s; q++)
+            for (int b = 0; b < B; b++) {
+                int64_t sb = ((int64_t)p * s + q) * B + b;
+                for (int hd = 0; hd < heads; hd++)
+                    for (int64_t blk = 0; blk < nblk; blk++) {
+                        int64_t j0 = blk * 128, j1 = j0 + 128 < Nsub ? j0 + 128 : Nsub;
+                        float amax = 0.0f;
+                        for (int64_t j = j0; j < j1; j++) {
+                            int64_t n = oracle_src_index(pattern, s, T, H, W, p, q, j);
+                            for (int d = 0; d < D; d++) {
+                                float v = (float)fabs(load_elem(x, ORACLE_BF16, ((int64_t)b * N + n) * C + (int64_t)hd * D + d));
+                                if (v > amax) amax = v;
+                            }
+                        }
+                        float scale = amax > 0.0f ? amax / 448.0f : 1.0f;
+                        float inv = amax > 0.0f ? 448.0f / amax : 1.0f;
+                        scales[(sb * heads + hd) * nblk + blk] = scale;
+                        for (int64_t j = j0; j < j1; j++) {
+                            int64_t n = oracle_src_index(pattern, s, T, H, W, p, q, j);
+                            for (int d = 0; d < D; d++) {
+                                float v = (float)load_elem(x, ORACLE_BF16, ((int64_t)b * N + n) * C + (int64_t)hd * D + d);
+                                float y = v * inv;
+                                if (y > 448.0f) y = 448.0f;
+                                if (y < -448.0f) y = -448.0f;
+                                x8[(sb * Nsub + j) * C + (int64_t)hd * D + d] = e4m3_encode(y);
+                            }
+                        }
+                    }
+            }
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

@@ -149,3 +149,38 @@ def skiparse_attn_fwd(q, k, v, T: int, H: int, W: int, s: int, pattern: str, sca
         "skiparse_attn_fwd",
     )
     return out
+
+
+def skiparse_quantize_fp8(x: torch.Tensor, T: int, H: int, W: int, s: int, pattern: str):
+    """bf16 [B][N][heads][D] (original layout) -> (uint8 E4M3 codes [s*s*B][N/s^2][heads][D] in the sparse layout,
+    float32 scales [s*s*B][heads][ceil(Nsub/128)])."""
+    B, heads, D = _dims(x, T, H, W)
+    if x.dtype != torch.bfloat16:
+        raise ValueError("skiparse_quantize_fp8 takes bf16 input")
+    nsub = (T * H * W) // (s * s)
+    x8 = torch.empty((s * s * B, nsub, heads, D), dtype=torch.uint8, device=x.device)
+    scales = torch.empty((s * s * B, heads, (nsub + 127) // 128), dtype=torch.float32, device=x.device)
+    _check(
+        lib().skiparse_quantize_fp8(_dev(x, "x"), _dev(x8, "x8"), _dev(scales, "scales"), B, heads, T, H, W, D, s,
+                                    PATTERNS[pattern], _stream()),
+        "skiparse_quantize_fp8",
+    )
+    return x8, scales
+
+
+def skiparse_attn_fwd_fp8(q8, k8, v8, sq, sk, sv, T: int, H: int, W: int, s: int, pattern: str, scale: float = 0.0,
+                          out: torch.Tensor | None = None):
+    """Attention on quantised sparse-layout tensors (from skiparse_quantize_fp8); bf16 output [B][N][heads][D] in the
+    original layout."""
+    SB, nsub, heads, D = q8.shape
+    B = SB // (s * s)
+    if SB != B * s * s or nsub * s * s != T * H * W:
+        raise ValueError("sparse-layout shape does not match the grid")
+    if out is None:
+        out = torch.empty((B, T * H * W, heads, D), dtype=torch.bfloat16, device=q8.device)
+    _check(
+        lib().skiparse_attn_fwd_fp8(_dev(q8, "q8"), _dev(k8, "k8"), _dev(v8, "v8"), _dev(sq, "sq"), _dev(sk, "sk"), _dev(sv, "sv"),
+                                    _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), _stream()),
+        "skiparse_attn_fwd_fp8",
+    )
+    return out

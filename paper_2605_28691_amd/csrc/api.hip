@@ -223,23 +223,38 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
 
 int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
                           int s, int pattern, void* stream) {
-    (void)stream;
     Shape sh;
     const int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
     if (rc != SKIPARSE_OK) return rc;
     if (!x_bf16 || !x8 || !scales) return SKIPARSE_EINVAL;
-    return SKIPARSE_EUNSUPPORTED;
+    if (misaligned(x_bf16) || misaligned(x8) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return SKIPARSE_EINVAL;
+    if (head_dim != 64 && head_dim != 128) return SKIPARSE_EUNSUPPORTED;
+    if (overlap2(x_bf16, sh.elems * 2, x8, sh.elems)) return SKIPARSE_EINVAL;
+    const GridMap g = make_gridmap(T, H, W, s, pattern);
+    return finish(launch_quantize_fp8(x_bf16, x8, scales, B, heads, head_dim, g, (hipStream_t)stream));
 }
 
 int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* sq, const float* sk, const float* sv,
                           void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
                           float scale, void* stream) {
-    (void)stream; (void)scale;
     Shape sh;
-    const int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
     if (rc != SKIPARSE_OK) return rc;
     if (!q8 || !k8 || !v8 || !sq || !sk || !sv || !out_bf16) return SKIPARSE_EINVAL;
-    return SKIPARSE_EUNSUPPORTED;
+    if (misaligned(q8) || misaligned(k8) || misaligned(v8) || misaligned(out_bf16)) return SKIPARSE_EINVAL;
+    if (head_dim != 64 && head_dim != 128) return SKIPARSE_EUNSUPPORTED;
+    rc = check_attn_ranges(sh, W, 2);
+    if (rc != SKIPARSE_OK) return rc;
+    if (overlap2(out_bf16, sh.elems * 2, q8, sh.elems) || overlap2(out_bf16, sh.elems * 2, k8, sh.elems) ||
+        overlap2(out_bf16, sh.elems * 2, v8, sh.elems))
+        return SKIPARSE_EINVAL;
+    Fp8AttnArgs a;
+    a.q8 = q8; a.k8 = k8; a.v8 = v8; a.sq = sq; a.sk = sk; a.sv = sv; a.out = out_bf16;
+    a.B = B; a.heads = heads; a.head_dim = head_dim;
+    a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+    a.n_blk = (uint32_t)((sh.n_sub + 127) / 128);
+    a.g = make_gridmap(T, H, W, s, pattern);
+    return finish(launch_attn_fp8(a, (hipStream_t)stream));
 }
 
 const char* skiparse_strerror(int code) {

@@ -1,0 +1,257 @@
+// FP8 (E4M3) flash-attention forward for gfx950: the 8-bit variant of the Skiparse attention path.
+//
+// Inputs are the quantised tensors in the sparse layout (one row of head_dim bytes per position and head) with one
+// float32 scale per (subsequence, head, block of 128 positions); the output is bf16 in the original layout.
+//     S = (q8 k8^T) * sq * sk * scale          logits, fp32
+//     P = exp(S - m)                           fp32, reference m raised lazily (only when it grew by more than 2^4)
+//     P8 = e4m3(P * sv / sv_max * 16)          the key block's V scale is folded into the probabilities
+//     O  = (P8 v8) * sv_max / 16 / sum(P)      fp32 accumulation, bf16 result
+// Both products use v_mfma_f32_32x32x64_f8f6f4 (64-deep contraction, twice the bf16 rate), transposed as in the bf16
+// kernel (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query.  A workgroup is 4 wavefronts x 32 queries = one
+// 128-position scale block of queries; keys are walked in tiles of 64, which never straddle a scale block.
+//   * The probabilities leave the accumulators as 16 values per 32-key block in the accumulator's key order (4h..4h+3,
+//     8+4h..); packed to bytes, one v_permlane32_swap per 16 keys turns that into 8 consecutive keys per lane half,
+//     which is the order ds_read_b64_tr_b8 (transposing LDS read for bytes) delivers V^T in.
+//   * K rows are padded to D+16 bytes and V rows to D+32 bytes in LDS so that the 16-byte fragment reads and the
+//     transposing reads spread over the banks.
+#include "kernels.h"
+
+namespace skiparse {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+
+constexpr int KT8 = 64;            // keys per tile = contraction depth of one PV MFMA
+constexpr float GROW_LOG2 = 4.0f;  // lazy reference update threshold: probabilities stay below 2^4
+constexpr float P_GAIN = 16.0f;    // probabilities are multiplied by (sv / sv_max) * 16 before the E4M3 cast: at most 256 < 448
+
+__device__ inline void lane_pair_f(float x, float& lo, float& hi) {
+    const unsigned a = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    const unsigned r0 = r[0], r1 = r[1];  // copy out before casting (see the bf16 kernel)
+    lo = __uint_as_float(r0);
+    hi = __uint_as_float(r1);
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
+    constexpr int NJ = D / 64;         // 64-channel MFMA steps of S^T = K Q^T
+    constexpr int MT = D / 32;         // 32-channel blocks of O^T
+    constexpr int K_STRIDE = D + 16;   // bytes
+    constexpr int V_STRIDE = D + 32;
+    constexpr int K_BYTES = KT8 * K_STRIDE, V_BYTES = KT8 * V_STRIDE;
+    constexpr int CPT = D / 64;        // 16-byte chunks per staging thread (4 threads per row)
+    __shared__ __attribute__((aligned(16))) char lds[2 * K_BYTES + 2 * V_BYTES];
+    __shared__ float sv_part[4];
+    char* const lds_k = lds;
+    char* const lds_v = lds + 2 * K_BYTES;
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t lq = lane & 31u, h = lane >> 5;
+    const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
+    const uint32_t ul = idx / q_tiles, qt = idx - ul * q_tiles;
+    const uint32_t unit = ul * 8u + xcd;  // unit = sb * heads + head
+    if (unit >= n_units) return;
+    const uint32_t sb = unit / (uint32_t)a.heads, head = unit - sb * (uint32_t)a.heads;
+    const uint32_t n_seq = (uint32_t)a.g.n_sub, n_blk = a.n_blk;
+    const size_t C = (size_t)a.heads * D;  // bytes per position in the sparse layout
+    const size_t unit_off = ((size_t)sb * n_seq) * C + (size_t)head * D;
+    const unsigned char* Qg = (const unsigned char*)a.q8 + unit_off;
+    const unsigned char* Kg = (const unsigned char*)a.k8 + unit_off;
+    const unsigned char* Vg = (const unsigned char*)a.v8 + unit_off;
+    const float* skp = a.sk + (size_t)unit * n_blk;
+    const float* svp = a.sv + (size_t)unit * n_blk;
+
+    // largest V scale of the unit: the probabilities carry sv / sv_max, the output is multiplied by sv_max at the end
+    float svm = 0.f;
+    for (uint32_t i = tid; i < n_blk; i += 256) svm = fmaxf(svm, svp[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) svm = fmaxf(svm, __shfl_xor(svm, off));
+    if (lane == 0) sv_part[wave] = svm;
+    __syncthreads();
+    const float sv_max = fmaxf(fmaxf(sv_part[0], sv_part[1]), fmaxf(sv_part[2], sv_part[3]));
+    const float p_gain = P_GAIN / sv_max;
+
+    // Q fragments: lane = query lq, 32 consecutive channels starting at 64*j + 32*h
+    const uint32_t jq = qt * 128u + wave * 32u + lq;
+    const bool q_valid = jq < n_seq;
+    const size_t q_off = (size_t)(q_valid ? jq : n_seq - 1u) * C;
+    i32x8 qf[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; j++) qf[j] = *(const i32x8*)(Qg + q_off + 64 * j + 32 * h);
+    const float cq = a.scale * 1.4426950408889634f * a.sq[(size_t)unit * n_blk + qt];  // the workgroup's queries are one scale block
+
+    // staging: 4 threads per row of a 64-key tile, CPT consecutive 16-byte chunks each
+    const uint32_t st_row = tid >> 2, st_piece = tid & 3u;
+    u32x4 kreg[CPT], vreg[CPT];
+    auto load_tile = [&](uint32_t t) {
+        uint32_t j = t * KT8 + st_row;
+        j = j < n_seq ? j : n_seq - 1u;
+        const size_t off = (size_t)j * C + (st_piece * CPT) * 16;
+#pragma unroll
+        for (int i = 0; i < CPT; i++) {
+            kreg[i] = *(const u32x4*)(Kg + off + i * 16);
+            vreg[i] = *(const u32x4*)(Vg + off + i * 16);
+        }
+    };
+    auto store_tile = [&](uint32_t buf) {
+#pragma unroll
+        for (int i = 0; i < CPT; i++) {
+            *(u32x4*)(lds_k + buf * K_BYTES + st_row * K_STRIDE + (st_piece * CPT + i) * 16) = kreg[i];
+            *(u32x4*)(lds_v + buf * V_BYTES + st_row * V_STRIDE + (st_piece * CPT + i) * 16) = vreg[i];
+        }
+    };
+
+    f32x16 oacc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) oacc[mt][r] = 0.f;
+    float m_ref = -INFINITY, l_run = 0.f;  // m_ref in log2 units of the scaled logits
+
+    const uint32_t k_rd = lq * K_STRIDE + 32 * h;  // + kt*32*K_STRIDE + 64*j
+    // transposing byte read: a 16-lane group covers 8 keys x 16 channels; lane i addresses key i/2, channels 8*(i%2)..
+    const uint32_t li = lane & 15u, lgrp = (lane >> 4) & 1u;
+    const uint32_t v_rd = (8 * h + (li >> 1)) * V_STRIDE + lgrp * 16 + 8 * (li & 1u);  // + g16*16*V_STRIDE + mt*32
+
+    const uint32_t n_kt = (n_seq + KT8 - 1) / KT8;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (uint32_t t = 0; t < n_kt; t++) {
+        const bool more = t + 1 < n_kt;
+        if (more) load_tile(t + 1);
+        const char* kb = lds_k + (t & 1u) * K_BYTES;
+        const char* vb = lds_v + (t & 1u) * V_BYTES;
+        const float ct = cq * skp[t >> 1];            // logits -> log2 units for this key block
+        const float pg = svp[t >> 1] * p_gain;        // V scale of this key block, relative to the largest, times the gain
+
+        // S^T = K Q^T: two blocks of 32 keys
+        f32x16 sacc[2];
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++) {
+#pragma unroll
+            for (int r = 0; r < 16; r++) sacc[kt][r] = 0.f;
+#pragma unroll
+            for (int j = 0; j < NJ; j++) {
+                const i32x8 kf = *(const i32x8*)(kb + k_rd + kt * 32 * K_STRIDE + 64 * j);
+                sacc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[j], sacc[kt], 0, 0, 0, 0, 0, 0);
+            }
+        }
+        if (!more && (n_seq % KT8) != 0) {
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const uint32_t key = t * KT8 + kt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    sacc[kt][r] = key < n_seq ? sacc[kt][r] : -INFINITY;
+                }
+        }
+        // online softmax
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) mx = fmaxf(mx, sacc[kt][r]);
+        float lo, hi;
+        lane_pair_f(mx, lo, hi);
+        const float m_new = fmaxf(m_ref, fmaxf(lo, hi) * ct);
+        const bool grow = m_new - m_ref > GROW_LOG2;  // same in lanes l and l^32
+        const bool any_grow = __builtin_amdgcn_ballot_w64(grow) != 0;
+        const float m_use = grow ? m_new : m_ref;
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_use);  // 1 where the reference stays, 0 on the first tile
+        m_ref = m_use;
+        float lsum = 0.f;
+        i32x8 pb;  // B operand of O^T += V^T P^T: 32 byte slots per lane half, slot 8*g16 + e <-> key 16*g16 + 8*h + e
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++) {
+            int w[4];  // dword i of the block: keys 8*i + 4*h + 0..3
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                float pe[4];
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    pe[e] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][4 * i + e], ct, -m_use));
+                    lsum += pe[e];
+                }
+                int pk = __builtin_amdgcn_cvt_pk_fp8_f32(pe[0] * pg, pe[1] * pg, 0, false);
+                w[i] = __builtin_amdgcn_cvt_pk_fp8_f32(pe[2] * pg, pe[3] * pg, pk, true);
+            }
+#pragma unroll
+            for (int m2 = 0; m2 < 2; m2++) {
+                // lanes l / l^32 hold keys (4h.., 8+4h..) of the 16-key group; after the swap each holds 8 consecutive keys
+                const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)w[2 * m2], (unsigned)w[2 * m2 + 1], false, false);
+                const unsigned s0 = sw[0], s1 = sw[1];
+                pb[(kt * 2 + m2) * 2] = (int)s0;
+                pb[(kt * 2 + m2) * 2 + 1] = (int)s1;
+            }
+        }
+        l_run = fmaf(l_run, alpha, lsum);
+        if (any_grow) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) oacc[mt][r] *= alpha;
+        }
+        // O^T += V^T P^T: one 64-key MFMA per 32-channel block
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            i32x8 vf;
+#pragma unroll
+            for (int g16 = 0; g16 < 4; g16++) {
+                const i32x2 t8 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(i32x2))(LDS_PTR(char))(vb + v_rd + g16 * 16 * V_STRIDE + mt * 32));
+                vf[2 * g16] = t8[0];
+                vf[2 * g16 + 1] = t8[1];
+            }
+            oacc[mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pb, oacc[mt], 0, 0, 0, 0, 0, 0);
+        }
+        if (more) store_tile((t + 1) & 1u);
+        __syncthreads();
+    }
+
+    // epilogue: O = O^T * sv_max / gain / l, bf16, scattered to the original layout
+    float llo, lhi;
+    lane_pair_f(l_run, llo, lhi);
+    const float inv = sv_max / (P_GAIN * (llo + lhi));
+    if (q_valid) {
+        const uint32_t pq = sb / (uint32_t)a.B, b0 = sb - pq * (uint32_t)a.B;
+        const uint32_t p = a.g.mode == MODE_DENSE ? 0u : pq / (uint32_t)a.g.s, q = a.g.mode == MODE_DENSE ? 0u : pq - p * (uint32_t)a.g.s;
+        const size_t row = (size_t)b0 * (uint32_t)a.g.n_tok + src_token(a.g, p, q, jq);
+        __bf16* orow = (__bf16*)a.out + row * C + (size_t)head * D;
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; e++) o[e] = (__bf16)(oacc[mt][g * 4 + e] * inv);
+                *(bf16x4*)(orow + mt * 32 + g * 8 + 4 * h) = o;
+            }
+    }
+}
+
+template <int D>
+static hipError_t launch_fp8_t(const Fp8AttnArgs& a, hipStream_t stream) {
+    const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
+    const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
+    const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 127u) / 128u;
+    const uint64_t blocks = (uint64_t)((n_units + 7u) / 8u * 8u) * q_tiles;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    attn_fwd_fp8_kernel<D><<<(uint32_t)blocks, 256, 0, stream>>>(a, q_tiles, n_units);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_fp8(const Fp8AttnArgs& a, hipStream_t stream) {
+    if (a.head_dim == 128) return launch_fp8_t<128>(a, stream);
+    if (a.head_dim == 64) return launch_fp8_t<64>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace skiparse

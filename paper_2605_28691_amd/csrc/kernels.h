@@ -29,4 +29,26 @@ struct AttnArgs {
 };
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
 
+// bf16 (original layout) -> E4M3 codes (sparse layout) + one float32 scale per (subsequence, head, 128 positions).
+hipError_t launch_quantize_fp8(const void* x, void* x8, float* scales, int B, int heads, int head_dim, const GridMap& g,
+                               hipStream_t stream);
+
+// FP8 flash-attention forward on the quantised sparse-layout tensors; bf16 output in the original layout.
+struct Fp8AttnArgs {
+    const void* q8;
+    const void* k8;
+    const void* v8;
+    const float* sq;
+    const float* sk;
+    const float* sv;
+    void* out;
+    int B;            // batch elements of the original layout
+    int heads;
+    int head_dim;
+    float scale;
+    uint32_t n_blk;   // scale blocks per (subsequence, head): ceil(n_sub / 128)
+    GridMap g;
+};
+hipError_t launch_attn_fp8(const Fp8AttnArgs& a, hipStream_t stream);
+
 }  // namespace skiparse
