@@ -21,7 +21,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+PEAK_FP8_TFLOPS = 5000.0
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the fused 768P kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/pmc_traffic_768p.txt):
+# FETCH_SIZE reads half the bytes of a copy kernel of known size on this chip, so it is scaled by 2.0; WRITE_SIZE by 1.0.
+MEASURED_TRAFFIC_BYTES = {"768p": (5.53972e6 * 2.0 + 806408.0) * 1024.0}
 # Paper context only (end-to-end model speed-ups on other hardware; Tab. 2): not comparable to a kernel figure.
 PAPER_CONTEXT = {"e2e_speedup_h200_bf16": 1.64, "e2e_speedup_ascend950pr_hif8_720p": 1.69, "e2e_speedup_ascend950pr_hif8_768p": 2.27}
 
@@ -120,7 +124,8 @@ def main() -> int:
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(flops / (kernel_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "algorithmic_bytes": 4 * qd.numel() * 2,
             "kernel": "attn_fwd_bf16_kernel<128>",
             "kernel_ms": round(kernel_ms, 4),
         },
@@ -153,6 +158,19 @@ def main() -> int:
         extras["dense_ms"] = round(d_ms, 4)
         extras["dense_tflops"] = round(w.dense_flops() / d_ms / 1e9, 2)
         extras["speedup_vs_dense"] = round(d_ms / ms, 3)
+        # ---- 8-bit variant on the same resident q, k, v: quantise (fused with the rearrangement), then fp8 attention
+        q8, sq = sk.skiparse_quantize_fp8(qd, T, H, W, s, "token")
+        k8, sk_ = sk.skiparse_quantize_fp8(kd, T, H, W, s, "token")
+        v8, sv = sk.skiparse_quantize_fp8(vd, T, H, W, s, "token")
+        qz_ms = time_calls(lambda: sk.skiparse_quantize_fp8(qd, T, H, W, s, "token"), 10, 2)
+        f8_ms = time_calls(lambda: sk.skiparse_attn_fwd_fp8(q8, k8, v8, sq, sk_, sv, T, H, W, s, "token", scale=w.scale, out=out), it, 1)
+        extras["fp8_quantize_ms_per_tensor"] = round(qz_ms, 4)
+        extras["fp8_quantize_GBps"] = round(3 * qd.numel() / qz_ms / 1e6, 1)  # 2 bytes read + 1 byte written per element
+        extras["fp8_attn_ms"] = round(f8_ms, 4)
+        extras["fp8_attn_tflops"] = round(flops / f8_ms / 1e9, 2)
+        extras["fp8_pct_of_fp8_mfma_peak"] = round(100.0 * flops / f8_ms / 1e9 / PEAK_FP8_TFLOPS, 2)
+        extras["fp8_speedup_vs_bf16"] = round(ms / f8_ms, 3)
+        out8 = out.clone()
         result["extras"] = extras
 
         # ---- oracle on the host cores, on a bounded sample of query rows of the same workload; doubles as parity check
@@ -180,6 +198,13 @@ def main() -> int:
             "extrapolated_full_call_s": round(cpu_s * (w.B * w.heads * w.N) / args.cpu_rows, 1),
         }
         result["parity"] = {"rows": args.cpu_rows, "max_abs": max_abs, "rel_l2": rel_l2, "ok": bool(max_abs <= 2e-2 and rel_l2 <= 5e-3)}
+        got8 = out8[r[:, 0], r[:, 2], r[:, 1]].cpu().to(torch.float64).numpy()
+        result["parity_fp8"] = {
+            "rows": args.cpu_rows,
+            "max_abs": float(np.abs(got8 - want).max()),
+            "rel_l2": float(np.linalg.norm(got8 - want) / np.linalg.norm(want)),
+            "note": "against the float64 oracle on the unquantised inputs; rel-L2 sits on the E4M3 rounding floor for i.i.d. Gaussian data",
+        }
 
     print(json.dumps(result))
     return 0
