@@ -25,7 +25,7 @@ PEAK_FP8_TFLOPS = 5000.0
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the fused 768P kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/pmc_traffic_768p.txt):
 # FETCH_SIZE reads half the bytes of a copy kernel of known size on this chip, so it is scaled by 2.0; WRITE_SIZE by 1.0.
-MEASURED_TRAFFIC_BYTES = {"768p": (5.53972e6 * 2.0 + 806408.0) * 1024.0}
+MEASURED_TRAFFIC_BYTES = {"768p": (5.63418e6 * 2.0 + 806411.0) * 1024.0}
 # Paper context only (end-to-end model speed-ups on other hardware; Tab. 2): not comparable to a kernel figure.
 PAPER_CONTEXT = {"e2e_speedup_h200_bf16": 1.64, "e2e_speedup_ascend950pr_hif8_720p": 1.69, "e2e_speedup_ascend950pr_hif8_768p": 2.27}
 
@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="768p", choices=["480p", "768p"])
     ap.add_argument("--cpu-rows", type=int, default=16384, help="query rows the oracle computes for cpu_baseline")
     ap.add_argument("--skip-extras", action="store_true", help="only the headline timing (used under the profiler)")
+    ap.add_argument("--extras", default="group,unfused,permute,dense,fp8,cpu",
+                    help="comma list of the extra sections to run: group, unfused, permute, dense, fp8, cpu (oracle baseline + parity)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -133,32 +135,39 @@ def main() -> int:
         "input_generation_s": round(gen_s, 1),
     }
 
-    if not args.skip_extras:
-        extras = {}
-        it = max(3, min(10, args.steps))
-        if "group" in w.patterns:
-            g_ms = time_calls(fused("group"), it, 1)
-            extras["fused_group_ms"] = round(g_ms, 4)
-            extras["fused_group_tflops"] = round(flops / g_ms / 1e9, 2)
+    sections = set() if args.skip_extras else {x for x in args.extras.split(",") if x}
+    extras = {}
+    it = max(3, min(10, args.steps))
+    out8 = None
+    tensor_bytes = qd.numel() * 2
+    if "group" in sections and "group" in w.patterns:
+        g_ms = time_calls(fused("group"), it, 1)
+        extras["fused_group_ms"] = round(g_ms, 4)
+        extras["fused_group_tflops"] = round(flops / g_ms / 1e9, 2)
+    if "unfused" in sections or "permute" in sections:
         need = sk.skiparse_workspace_bytes(w.B, w.heads, T, H, W, w.D, s, False)
         ws = torch.empty(need, dtype=torch.uint8, device="cuda")
-        u_ms = time_calls(lambda: sk.skiparse_attn_fwd(qd, kd, vd, T, H, W, s, "token", scale=w.scale, fused=False, out=out, workspace=ws), it, 1)
-        extras["unfused_token_ms"] = round(u_ms, 4)
-        yp = ws[: qd.numel() * 2].view(torch.bfloat16).view(s * s * w.B, w.Nsub, w.heads, w.D)
-        p_ms = time_calls(lambda: sk.skiparse_permute(qd, T, H, W, s, "token", out=yp), 10, 2)
-        up_ms = time_calls(lambda: sk.skiparse_unpermute(yp, T, H, W, s, "token", out=out), 10, 2)
-        tensor_bytes = qd.numel() * 2
-        extras["permute_ms"] = round(p_ms, 4)
-        extras["permute_GBps"] = round(2 * tensor_bytes / p_ms / 1e6, 1)
-        extras["unpermute_ms"] = round(up_ms, 4)
-        extras["unpermute_GBps"] = round(2 * tensor_bytes / up_ms / 1e6, 1)
-        extras["permute_frac_of_hbm_peak"] = round(2 * tensor_bytes / p_ms / 1e6 / PEAK_HBM_GBS, 4)
-        del ws, yp
+        if "unfused" in sections:
+            u_ms = time_calls(lambda: sk.skiparse_attn_fwd(qd, kd, vd, T, H, W, s, "token", scale=w.scale, fused=False, out=out, workspace=ws), it, 1)
+            extras["unfused_token_ms"] = round(u_ms, 4)
+        if "permute" in sections:
+            yp = ws[:tensor_bytes].view(torch.bfloat16).view(s * s * w.B, w.Nsub, w.heads, w.D)
+            p_ms = time_calls(lambda: sk.skiparse_permute(qd, T, H, W, s, "token", out=yp), 10, 2)
+            up_ms = time_calls(lambda: sk.skiparse_unpermute(yp, T, H, W, s, "token", out=out), 10, 2)
+            extras["permute_ms"] = round(p_ms, 4)
+            extras["permute_GBps"] = round(2 * tensor_bytes / p_ms / 1e6, 1)  # one read and one write of the tensor
+            extras["unpermute_ms"] = round(up_ms, 4)
+            extras["unpermute_GBps"] = round(2 * tensor_bytes / up_ms / 1e6, 1)
+            extras["permute_frac_of_hbm_peak"] = round(2 * tensor_bytes / p_ms / 1e6 / PEAK_HBM_GBS, 4)
+            del yp
+        del ws
+    if "dense" in sections:
         d_ms = time_calls(lambda: sk.dense_attn_fwd(qd, kd, vd, T, H, W, scale=w.scale, out=out), 3, 1)
         extras["dense_ms"] = round(d_ms, 4)
         extras["dense_tflops"] = round(w.dense_flops() / d_ms / 1e9, 2)
         extras["speedup_vs_dense"] = round(d_ms / ms, 3)
-        # ---- 8-bit variant on the same resident q, k, v: quantise (fused with the rearrangement), then fp8 attention
+    if "fp8" in sections:
+        # 8-bit variant on the same resident q, k, v: quantise (fused with the rearrangement), then fp8 attention
         q8, sq = sk.skiparse_quantize_fp8(qd, T, H, W, s, "token")
         k8, sk_ = sk.skiparse_quantize_fp8(kd, T, H, W, s, "token")
         v8, sv = sk.skiparse_quantize_fp8(vd, T, H, W, s, "token")
@@ -171,9 +180,12 @@ def main() -> int:
         extras["fp8_pct_of_fp8_mfma_peak"] = round(100.0 * flops / f8_ms / 1e9 / PEAK_FP8_TFLOPS, 2)
         extras["fp8_speedup_vs_bf16"] = round(ms / f8_ms, 3)
         out8 = out.clone()
+        del q8, k8, v8
+    if extras:
         result["extras"] = extras
 
-        # ---- oracle on the host cores, on a bounded sample of query rows of the same workload; doubles as parity check
+    if "cpu" in sections:
+        # oracle on the host cores, on a bounded sample of query rows of the same workload; doubles as parity check
         import oracle
 
         fused("token")()
@@ -198,13 +210,14 @@ def main() -> int:
             "extrapolated_full_call_s": round(cpu_s * (w.B * w.heads * w.N) / args.cpu_rows, 1),
         }
         result["parity"] = {"rows": args.cpu_rows, "max_abs": max_abs, "rel_l2": rel_l2, "ok": bool(max_abs <= 2e-2 and rel_l2 <= 5e-3)}
-        got8 = out8[r[:, 0], r[:, 2], r[:, 1]].cpu().to(torch.float64).numpy()
-        result["parity_fp8"] = {
-            "rows": args.cpu_rows,
-            "max_abs": float(np.abs(got8 - want).max()),
-            "rel_l2": float(np.linalg.norm(got8 - want) / np.linalg.norm(want)),
-            "note": "against the float64 oracle on the unquantised inputs; rel-L2 sits on the E4M3 rounding floor for i.i.d. Gaussian data",
-        }
+        if out8 is not None:
+            got8 = out8[r[:, 0], r[:, 2], r[:, 1]].cpu().to(torch.float64).numpy()
+            result["parity_fp8"] = {
+                "rows": args.cpu_rows,
+                "max_abs": float(np.abs(got8 - want).max()),
+                "rel_l2": float(np.linalg.norm(got8 - want) / np.linalg.norm(want)),
+                "note": "against the float64 oracle on the unquantised inputs; rel-L2 sits on the E4M3 rounding floor for i.i.d. Gaussian data",
+            }
 
     print(json.dumps(result))
     return 0
