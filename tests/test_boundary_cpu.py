@@ -96,3 +96,26 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(sk, "_LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         sk.lib()
+
+
+def test_fp8_entry_points_reject_bad_arguments(lib):
+    a = [ctypes.c_void_p(FAKE + i * (1 << 30)) for i in range(8)]
+    f = ctypes.c_float(0.0)
+    assert lib.skiparse_quantize_fp8(None, a[1], a[2], 1, 2, 2, 8, 8, 64, 2, 0, None) == -1
+    assert lib.skiparse_quantize_fp8(a[0], a[1], a[2], 1, 2, 2, 6, 8, 64, 2, 1, None) == -2  # group-wise needs H % 4 == 0
+    assert lib.skiparse_quantize_fp8(a[0], a[1], a[2], 1, 2, 2, 8, 8, 96, 2, 0, None) == -3  # head_dim 96
+    assert lib.skiparse_quantize_fp8(a[0], a[0], a[2], 1, 2, 2, 8, 8, 64, 2, 0, None) == -1  # output aliases input
+    ok = [1, 2, 2, 8, 8, 64, 2, 0]
+    assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], None, a[6], *ok, f, None) == -1
+    assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], a[5], a[0], *ok, f, None) == -1  # out aliases q8
+    assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], a[5], a[6], 1, 2, 2, 8, 8, 32, 2, 0, f, None) == -3
+    assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], a[5], a[6], 1, 2, 2, 8, 7, 64, 2, 0, f, None) == -2
+
+
+def test_attention_rejects_out_of_range_sizes(lib):
+    a = [ctypes.c_void_p(FAKE + i * (1 << 40)) for i in range(4)]
+    f = ctypes.c_float(0.0)
+    # 2^24 tokens per batch element: beyond the 24-bit multiplies of the attention kernels' address arithmetic
+    assert lib.dense_attn_fwd(a[0], a[1], a[2], a[3], 1, 1, 1 << 8, 1 << 8, 1 << 8, 64, f, 0, None) == -2
+    # one batch element of 4 GiB or more: beyond the 32-bit row offsets
+    assert lib.dense_attn_fwd(a[0], a[1], a[2], a[3], 1, 64, 1 << 6, 1 << 6, 1 << 6, 128, f, 0, None) == -2
