@@ -5,31 +5,35 @@
 // without ever forming the N x N matrix: keys are walked in blocks of 32 with a running row maximum and row sum.
 //
 // Mapping onto the hardware
-//   * One workgroup = 4 wavefronts; each wavefront owns 32 query rows for the whole key walk; two workgroups share a
-//     CU (<= 256 VGPRs, 74 KiB LDS each), so every SIMD interleaves two independent wavefronts.
+//   * One workgroup = 8 wavefronts (two per SIMD), each owning 32 query rows for the whole key walk: 256 queries share
+//     every K/V tile that is brought into LDS, which halves the L2 -> LDS traffic per MFMA compared with 128 queries.
+//     One workgroup per CU (<= 256 VGPRs per lane, 74 KiB LDS).
 //   * The products are formed transposed, S^T = K Q^T and O^T = V^T P^T, with v_mfma_f32_32x32x16_bf16.  In the
 //     32x32 accumulator layout lane l holds column l%32, so every lane owns ONE query: its 16 registers per 32-key
-//     block are 16 keys of that query, the row maximum and sum are in-lane loops plus one exchange with lane l^32,
-//     and the exponentiated accumulator registers, rounded to bf16, ARE the B operand of the second product -- the
-//     probabilities never leave registers.  The key order inside a 16-key MFMA step is whatever the accumulator
-//     layout gives (keys 4h..4h+3 and 8+4h..8+4h+3 for lane half h); V^T is fetched in the same order.
+//     block are 16 keys of that query, and the exponentiated accumulator registers, rounded to bf16, ARE the B operand
+//     of the second product -- the probabilities never leave registers.  The key order inside a 16-key MFMA step is
+//     whatever the accumulator layout gives (keys 4h..4h+3 and 8+4h..8+4h+3 for lane half h); V^T is fetched in the
+//     same order.
 //   * Software pipeline over 32-key blocks: step b issues the MFMAs of  S(b+1) = K(b+1) Q^T  and  O += V(b-1)^T P(b-1)^T
 //     and does the softmax arithmetic of block b on the vector ALU.  The three are independent inside a step, so the
 //     matrix pipe and the vector ALU overlap within one wavefront as well as across the two on a SIMD.
 //   * In the steady state the instruction order of a step is written out by hand and fixed with scheduling fences:
-//     the PV MFMAs first, with the block maximum and the reference update between them, then the QK MFMAs with two
-//     pairs of exponentials between each, and every LDS fragment read two MFMAs before its use.
+//     MFMAs of the two products alternate (so consecutive MFMAs never depend on each other), each followed by its share
+//     of the exponentials, and every LDS fragment is read three MFMAs before its use.
+//   * Reference maximum without a per-block maximum: the exponentials are taken against the reference the row already
+//     has; the common path computes no maximum at all.  The guard is the row sum: if 16 probabilities of a lane add up
+//     to 2^16 or more (always on the first block, where the reference is -inf) the wavefront takes a rare path that finds
+//     the true maximum, redoes the block against it and rescales l; O is rescaled at the start of the next step in a
+//     block that holds only the in-place multiplies.  Numerator and denominator always use the same reference, so the
+//     result is exact up to rounding; probabilities up to 2^16 keep their relative precision in bf16, O and l are fp32.
 //   * K and V tiles of 64 keys are staged global -> registers -> LDS, double buffered, K one tile ahead of V (a
 //     window of two steps reads K tile W and V tile W-1), one barrier per window; the global loads of a tile are issued
-//     a whole window before their LDS stores.  K is read back as the A operand
-//     with 16-byte reads (rows padded to D*2+16 bytes); V^T is read with ds_read_b64_tr_b16, the gfx950 transposing
-//     LDS read (rows padded to D*2+64 bytes), so V stays row-major in LDS.
-//   * Lazy rescale: the reference maximum of a row is raised only when it grew by more than 2^8 in some lane of the
-//     wavefront, so multiplying the O accumulators by the correction is a rare, separate block.  Numerator and
-//     denominator always use the same reference, so the result is exact up to rounding.
-//   * Row addresses come from src_token(): in the dense mode position j is row j, in the sparse modes it is the
-//     token the Skiparse rearrangement (Algorithm 1) would have put at position j, so q, k, v are read and out is
-//     written in the original layout and no permuted copy exists.  One thread stages one row per tile and advances its
+//     a whole window before their LDS stores.  K is read back as the A operand with 16-byte reads (rows padded to
+//     D*2+16 bytes); V^T is read with ds_read_b64_tr_b16, the gfx950 transposing LDS read (rows padded to D*2+64
+//     bytes), so V stays row-major in LDS.
+//   * Row addresses come from the Skiparse index map: in the dense mode position j is row j, in the sparse modes it is
+//     the token the rearrangement (Algorithm 1) would have put at position j, so q, k, v are read and out is written in
+//     the original layout and no permuted copy exists.  A thread stages part of one row per tile and advances its
 //     (row, column) position by 64 keys with adds and one wrap, so the index arithmetic is a handful of full-rate
 //     24-bit multiply-adds per thread per 64 keys.
 //   * Workgroups are numbered so that all query tiles of one unit run on the same XCD (workgroup id mod 8 selects
@@ -50,13 +54,17 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
 constexpr int KT = 64;          // keys per staged tile (two 32-key blocks)
-constexpr int NTHREADS = 256;   // 4 wavefronts
+constexpr int NW = 8;            // wavefronts per workgroup: two per SIMD, all sharing one K/V tile in LDS
+constexpr int NTHREADS = 64 * NW;
+constexpr int ATTN_QT = 1;       // 32-query tiles per wavefront
+constexpr int LDS_AHEAD = 3;     // MFMA groups by which the LDS fragment reads run ahead in the steady state
 constexpr float RESCALE_LOG2 = 8.0f;  // the reference maximum is only raised when it grew by more than 2^8
 
 template <int D>
 struct Tile {
     static constexpr int CH = D / 8;                     // 16-byte chunks per row
-    static constexpr int CPT = CH / 4;                   // chunks per thread: 4 threads stage one row
+    static constexpr int TPR = NTHREADS / KT;            // threads that stage one row of a 64-key tile
+    static constexpr int CPT = CH / TPR;                 // 16-byte chunks per thread
     static constexpr int K_STRIDE = D * 2 + 16;          // bytes; +16 spreads the 16-byte reads of 16 rows over all banks
     static constexpr int V_STRIDE = D * 2 + 64;          // bytes; +64 keeps the 4 rows of a transposing read on distinct banks
     static constexpr int K_BYTES = KT * K_STRIDE;
@@ -88,11 +96,11 @@ __device__ inline size_t uniform(size_t x) {
 
 // GROUP selects the group-wise index map (two extra divisions by s per staged row); token-wise and dense use GROUP = false.
 template <int D, int QT, bool GROUP>
-__global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
+__global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
     using TL = Tile<D>;
     constexpr int KS = D / 16;     // MFMA steps along head_dim for S^T = K Q^T
     constexpr int MT = D / 32;     // 32-row blocks of O^T
-    constexpr int BR = 128 * QT;   // query rows per workgroup: QT tiles of 32 per wavefront
+    constexpr int BR = 32 * NW * QT;   // query rows per workgroup: QT tiles of 32 per wavefront
     __shared__ __attribute__((aligned(16))) char lds[2 * TL::K_BYTES + 2 * TL::V_BYTES];
     char* const lds_k = lds;
     char* const lds_v = lds + 2 * TL::K_BYTES;
@@ -134,9 +142,9 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
         for (int ks = 0; ks < KS; ks++) qf[qi][ks] = *(const bf16x8*)(Qg + q_row_off[qi] + ks * 16 + 8 * h);
     }
 
-    // ---- staging: 4 threads per row of a 64-key tile.  K chunks of a thread are contiguous (st_piece*CPT + i), V chunks
-    // are interleaved (st_piece + 4*i): with the two row paddings each choice makes the 16-byte LDS stores conflict free.
-    const uint32_t st_row = tid >> 2, st_piece = tid & 3u;
+    // ---- staging: TPR threads per row of a 64-key tile.  K chunks of a thread are contiguous (st_piece*CPT + i), V chunks
+    // are interleaved (st_piece + TPR*i).
+    const uint32_t st_row = tid / TL::TPR, st_piece = tid % TL::TPR;
     u32x4 kreg[TL::CPT], vreg[TL::CPT];  // staging registers: loaded during one window, stored to LDS at the start of the next
     // Byte offset of this thread's row of a tile, relative to the unit's base (fits 32 bits: checked on the host).
     // Tiles are visited in order, so (r, ws) = (j / Ws, j % Ws) of the row are advanced by 64 positions with adds and one
@@ -175,7 +183,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
     };
     auto load_v = [&](uint32_t off) {
 #pragma unroll
-        for (int i = 0; i < TL::CPT; i++) vreg[i] = *(const u32x4*)((const char*)Vg + off + (st_piece + 4 * i) * 16);
+        for (int i = 0; i < TL::CPT; i++) vreg[i] = *(const u32x4*)((const char*)Vg + off + (st_piece + TL::TPR * i) * 16);
     };
     auto store_k = [&](uint32_t buf) {
 #pragma unroll
@@ -185,7 +193,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
     auto store_v = [&](uint32_t buf) {
 #pragma unroll
         for (int i = 0; i < TL::CPT; i++)
-            *(u32x4*)(lds_v + buf * TL::V_BYTES + st_row * TL::V_STRIDE + (st_piece + 4 * i) * 16) = vreg[i];
+            *(u32x4*)(lds_v + buf * TL::V_BYTES + st_row * TL::V_STRIDE + (st_piece + TL::TPR * i) * 16) = vreg[i];
     };
 
     // ---- running state: every lane tracks its own query (lanes l and l^32 hold the same m_ref; l_run is a partial sum)
@@ -203,6 +211,23 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
             for (int r = 0; r < 16; r++) oacc[qi][mt][r] = 0.f;
     }
     const float c = a.scale * 1.4426950408889634f;  // logits are kept raw; exp(x*scale) = exp2(x*c)
+    // A raised reference rescales O one step late: the factor is kept here and applied at the start of the next step
+    // (after PV(b-1), before PV(b)), in a block of its own that holds nothing but the in-place multiplies.
+    float alpha_pending[QT];
+    bool pending = false;  // wave-uniform
+#pragma unroll
+    for (int qi = 0; qi < QT; qi++) alpha_pending[qi] = 1.f;
+    auto apply_pending = [&]() {
+        if (__builtin_expect(pending, 0)) {
+#pragma unroll
+            for (int qi = 0; qi < QT; qi++)
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) oacc[qi][mt][r] *= alpha_pending[qi];
+            pending = false;
+        }
+    };
 
     // LDS read offsets that do not depend on the tile
     const uint32_t k_rd = lq * TL::K_STRIDE + h * 16;  // + half*32*K_STRIDE + ks*32
@@ -269,9 +294,8 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
     // the compiler.  The steady-state windows use step_manual below.
     auto step = [&](auto DO_QK, auto DO_PV, auto MASK, auto PARC, uint32_t blk, const char* kb, const char* vb) {
         constexpr int PAR = decltype(PARC)::value;
+        apply_pending();
         if (decltype(DO_QK)::value) qk(kb, PAR ^ 1, sreg[PAR ^ 1]);
-        float lsum[QT], m_new[QT];
-        bool grow[QT];
         unsigned long long grow_mask = 0;
 #pragma unroll
         for (int qi = 0; qi < QT; qi++) {
@@ -287,106 +311,110 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
                                    max3(max3(s[9], s[10], s[11]), max3(s[12], s[13], s[14]), s[15]));
             float lo, hi;
             lane_pair(mx, lo, hi);
-            m_new[qi] = max3(m_ref[qi], lo, hi);
-            grow[qi] = (m_new[qi] - m_ref[qi]) * c > RESCALE_LOG2;  // same in lanes l and l^32
-            grow_mask |= __builtin_amdgcn_ballot_w64(grow[qi]);
-            const float m_use = grow[qi] ? m_new[qi] : m_ref[qi];
-            m_new[qi] = __builtin_amdgcn_exp2f((m_ref[qi] - m_use) * c);  // alpha: 1 where the reference stays, 0 on the first block
+            const float m_new = max3(m_ref[qi], lo, hi);
+            const bool grow = (m_new - m_ref[qi]) * c > RESCALE_LOG2;  // same in lanes l and l^32
+            grow_mask |= __builtin_amdgcn_ballot_w64(grow);
+            const float m_use = grow ? m_new : m_ref[qi];
+            alpha_pending[qi] = __builtin_amdgcn_exp2f((m_ref[qi] - m_use) * c);  // 1 where the reference stays, 0 on the first block
             m_ref[qi] = m_use;
-            l_run[qi] = fmaf(l_run[qi], m_new[qi], exps(s, m_use * c, preg[PAR][qi]));
+            l_run[qi] = fmaf(l_run[qi], alpha_pending[qi], exps(s, m_use * c, preg[PAR][qi]));
         }
         if (decltype(DO_PV)::value) pv(vb, PAR ^ 1, preg[PAR ^ 1]);
-        // The probabilities are only consumed by the next step; pin them here so that their computation stays in
-        // this step's block (next to the MFMAs it overlaps with) instead of sinking below the branch.
+        pending = grow_mask != 0;  // O is rescaled at the start of the next step: after PV(b-1), before PV(b)
+    };
+    // Hand-ordered version of a full, unmasked step: the instruction order is fixed group by group with scheduling
+    // fences, and the exponentials are taken against the reference the row already has, so the common path computes no
+    // maximum at all: per key only fma, exp, half a bf16 pack and half a dot2 (row sum).  The guard is the row sum itself:
+    // if a lane's 16 probabilities add up to 2^16 or more (always on the first block, where the reference is -inf), the
+    // wavefront takes the rare path, which finds the true maximum, redoes the block's exponentials against it and rescales
+    // O and l.  Probabilities up to 2^16 are harmless: bf16 keeps their relative precision and O, l are fp32.
+    // LDS fragments are read two MFMA groups ahead and every fragment feeds the MFMAs of all QT query tiles.
+    auto step_manual = [&](auto PARC, const char* kb, const char* vb) {
+        constexpr int PAR = decltype(PARC)::value;
+        constexpr int NPV = 2 * MT, NQK = KS, NG = NPV + NQK;
+        // MFMA groups alternate between the two products (PV, QK, PV, QK, ...: NPV == NQK), so consecutive MFMAs never
+        // depend on each other: group g is PV group g/2 when g is even and QK group g/2 when g is odd.
+        static_assert(NPV == NQK, "the two products have the same number of MFMA groups");
+        auto read_frag = [&](int g) -> bf16x8 {
+            const int i = g / 2;
+            if (g % 2 == 0) {  // fragment of PV group i: 16-key group m2 = i / MT, channel block mt = i % MT
+                const char* va = vb + v_rd + ((PAR ^ 1) * 32 + (i / MT) * 16) * TL::V_STRIDE + (i % MT) * 64;
+                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))va);
+                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + 8 * TL::V_STRIDE));
+                return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+            return *(const bf16x8*)(kb + k_rd + (PAR ^ 1) * 32 * TL::K_STRIDE + i * 32);
+        };
+        apply_pending();
+        bf16x8 fr[NG];  // every fragment has its own name; lifetimes are short, so few registers are live at a time
 #pragma unroll
-        for (int qi = 0; qi < QT; qi++) asm volatile("" ::"v"(preg[PAR][qi][0]), "v"(preg[PAR][qi][1]));
-        if (__builtin_expect(grow_mask != 0, 0)) {
+        for (int g = 0; g < LDS_AHEAD; g++) fr[g] = read_frag(g);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 acc[QT];
+        float lsum[QT], mc[QT];
+        bf16x8 pk[QT][2];
+#pragma unroll
+        for (int qi = 0; qi < QT; qi++) {
+            lsum[qi] = 0.f;
+            mc[qi] = m_ref[qi] * c;
+        }
+#pragma unroll
+        for (int g = 0; g < NG; g++) {
+            if (g + LDS_AHEAD < NG) fr[g + LDS_AHEAD] = read_frag(g + LDS_AHEAD);
+            const int i = g / 2;
 #pragma unroll
             for (int qi = 0; qi < QT; qi++) {
-                const float alpha = m_new[qi];
+                if (g % 2 == 0) {
+                    oacc[qi][i % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g], preg[PAR ^ 1][qi][i / MT], oacc[qi][i % MT], 0, 0, 0);
+                } else {
+                    if (i == 0) {
 #pragma unroll
-                for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) oacc[qi][mt][r] *= alpha;  // after PV(b-1), before PV(b)
+                        for (int r = 0; r < 16; r++) acc[qi][r] = 0.f;
+                    }
+                    acc[qi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g], qf[qi][i], acc[qi], 0, 0, 0);
+                }
             }
-        }
-    };
-    // Hand-ordered version of a full, unmasked step (QT = 1): the instruction order is fixed group by group with scheduling
-    // fences.  PV(b-1) MFMAs run first while the vector ALU finds the block maximum and settles the reference; the QK(b+1)
-    // MFMAs follow while the exponentials are taken, two pairs per MFMA.  LDS fragments are read two MFMAs ahead.
-    auto step_manual = [&](auto PARC, const char* kb, const char* vb) {
-        static_assert(QT == 1, "manual schedule is written for one query tile per wavefront");
-        constexpr int PAR = decltype(PARC)::value;
-        constexpr int NPV = 2 * MT, NQK = KS;
-        f32x16& s = sreg[PAR][0];
-        const bf16x8(&pp)[2] = preg[PAR ^ 1][0];
-        auto read_v = [&](int i) -> bf16x8 {  // fragment of PV MFMA i: 16-key group m2 = i / MT, channel block mt = i % MT
-            const char* va = vb + v_rd + ((PAR ^ 1) * 32 + (i / MT) * 16) * TL::V_STRIDE + (i % MT) * 64;
-            const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))va);
-            const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + 8 * TL::V_STRIDE));
-            return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-        };
-        auto read_k = [&](int ks) -> bf16x8 { return *(const bf16x8*)(kb + k_rd + (PAR ^ 1) * 32 * TL::K_STRIDE + ks * 32); };
-        bf16x8 fr[NPV + NQK];  // every fragment has its own name; lifetimes are short, so few registers are live at a time
-        fr[0] = read_v(0);
-        fr[1] = read_v(1);
-        __builtin_amdgcn_sched_barrier(0);
-        // --- phase 1: PV MFMAs; maximum of the block and the new reference
-        float t0, t1, t2, t3, t4, mx = 0.f, lo = 0.f, hi = 0.f, m_new = 0.f, alpha = 1.f, mc = 0.f;
-        bool grow = false;
+            // this group's share of the exponentials: 16 / NG pairs of keys per query tile, rounded so that all 16 are covered
 #pragma unroll
-        for (int i = 0; i < NPV; i++) {
-            if (i + 2 < NPV) fr[i + 2] = read_v(i + 2);
-            else fr[i + 2] = read_k(i + 2 - NPV);
-            oacc[0][i % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i], pp[i / MT], oacc[0][i % MT], 0, 0, 0);
-            const int slot = i * 8 / NPV;  // spread the 8 chain slots over the PV MFMAs
-            const int slot_end = (i + 1) * 8 / NPV;
+            for (int qi = 0; qi < QT; qi++) {
+                const f32x16& s = sreg[PAR][qi];
 #pragma unroll
-            for (int c8 = slot; c8 < slot_end; c8++) {
-                if (c8 == 0) { t0 = max3(s[0], s[1], s[2]); t1 = max3(s[3], s[4], s[5]); t2 = max3(s[6], s[7], s[8]); }
-                if (c8 == 1) { t3 = max3(s[9], s[10], s[11]); t4 = max3(s[12], s[13], s[14]); t0 = max3(t0, t1, t2); }
-                if (c8 == 2) { mx = fmaxf(max3(t3, t4, s[15]), t0); }
-                if (c8 == 3) { lane_pair(mx, lo, hi); }
-                if (c8 == 4) { m_new = max3(m_ref[0], lo, hi); grow = (m_new - m_ref[0]) * c > RESCALE_LOG2; }
-                if (c8 == 5) {
-                    const float m_use = grow ? m_new : m_ref[0];
-                    alpha = __builtin_amdgcn_exp2f((m_ref[0] - m_use) * c);
-                    m_ref[0] = m_use;
-                    mc = m_use * c;
+                for (int e = 2 * (g * 8 / NG); e < 2 * ((g + 1) * 8 / NG); e += 2) {
+                    const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, -mc[qi])), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, -mc[qi]))};
+                    const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
+                    lsum[qi] = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum[qi], false);
+                    pk[qi][e / 8][e % 8] = pb[0];
+                    pk[qi][e / 8][e % 8 + 1] = pb[1];
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        // --- phase 2: QK MFMAs; exponentials, 16 / NQK per MFMA
-        f32x16 acc;
+        unsigned long long redo = 0;
 #pragma unroll
-        for (int r = 0; r < 16; r++) acc[r] = 0.f;
-        float lsum = 0.f;
-        bf16x8 pk[2];
-#pragma unroll
-        for (int i = 0; i < NQK; i++) {
-            if (i + 2 < NQK) fr[NPV + i + 2] = read_k(i + 2);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[NPV + i], qf[0][i], acc, 0, 0, 0);
-#pragma unroll
-            for (int e = i * 16 / NQK; e < (i + 1) * 16 / NQK; e += 2) {
-                const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, -mc))};
-                const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
-                lsum = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum, false);
-                pk[e / 8][e % 8] = pb[0];
-                pk[e / 8][e % 8 + 1] = pb[1];
-            }
-            __builtin_amdgcn_sched_barrier(0);
+        for (int qi = 0; qi < QT; qi++) {
+            sreg[PAR ^ 1][qi] = acc[qi];
+            preg[PAR][qi][0] = pk[qi][0];
+            preg[PAR][qi][1] = pk[qi][1];
+            asm volatile("" ::"v"(preg[PAR][qi][0]), "v"(preg[PAR][qi][1]));
+            redo |= __builtin_amdgcn_ballot_w64(!(lsum[qi] < 65536.0f));  // also catches inf and NaN
         }
-        sreg[PAR ^ 1][0] = acc;
-        preg[PAR][0][0] = pk[0];
-        preg[PAR][0][1] = pk[1];
-        l_run[0] = fmaf(l_run[0], alpha, lsum);
-        asm volatile("" ::"v"(preg[PAR][0][0]), "v"(preg[PAR][0][1]));
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
+        if (__builtin_expect(redo != 0, 0)) {
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++)
+            for (int qi = 0; qi < QT; qi++) {
+                const f32x16& s = sreg[PAR][qi];
+                const float mx = fmaxf(max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8])),
+                                       max3(max3(s[9], s[10], s[11]), max3(s[12], s[13], s[14]), s[15]));
+                float lo, hi;
+                lane_pair(mx, lo, hi);
+                const float m_new = max3(m_ref[qi], lo, hi);
+                alpha_pending[qi] = __builtin_amdgcn_exp2f((m_ref[qi] - m_new) * c);  // 0 on the first block
+                m_ref[qi] = m_new;
+                l_run[qi] = fmaf(l_run[qi], alpha_pending[qi], exps(s, m_new * c, preg[PAR][qi]));
+            }
+            pending = true;
+        } else {
 #pragma unroll
-                for (int r = 0; r < 16; r++) oacc[0][mt][r] *= alpha;
+            for (int qi = 0; qi < QT; qi++) l_run[qi] += lsum[qi];
         }
     };
     using T_ = std::true_type;
@@ -449,6 +477,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 ? 2 : 1)) void attn_fwd_bf16_ker
     {
         const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
         step(F_{}, T_{}, T_{}, P1{}, 2 * W - 1, nullptr, vb);
+        apply_pending();
         pv(vb, 1, preg[1]);
     }
 
@@ -476,7 +505,7 @@ template <int D, int QT, bool GROUP>
 static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
-    const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 128u * QT - 1u) / (128u * QT);
+    const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 32u * NW * QT - 1u) / (32u * NW * QT);
     const uint32_t units_padded = (n_units + 7u) / 8u * 8u;
     const uint64_t blocks = (uint64_t)units_padded * q_tiles;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
@@ -486,8 +515,8 @@ static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
     const bool group = a.g.b != 0;
-    if (a.head_dim == 128) return group ? launch_t<128, 1, true>(a, stream) : launch_t<128, 1, false>(a, stream);
-    if (a.head_dim == 64) return group ? launch_t<64, 1, true>(a, stream) : launch_t<64, 1, false>(a, stream);
+    if (a.head_dim == 128) return group ? launch_t<128, ATTN_QT, true>(a, stream) : launch_t<128, ATTN_QT, false>(a, stream);
+    if (a.head_dim == 64) return group ? launch_t<64, ATTN_QT, true>(a, stream) : launch_t<64, ATTN_QT, false>(a, stream);
     return hipErrorInvalidValue;
 }
 
