@@ -3,12 +3,13 @@
 // Inputs are the quantised tensors in the sparse layout (one row of head_dim bytes per position and head) with one
 // float32 scale per (subsequence, head, block of 128 positions); the output is bf16 in the original layout.
 //     S = (q8 k8^T) * sq * sk * scale          logits, fp32
-//     P = exp(S - m)                           fp32, reference m raised lazily (only when it grew by more than 2^4)
+//     P = exp(S - m)                           fp32; the reference m is only raised when the scaled probabilities of a tile
+//                                              would not fit E4M3 (row-sum guard, see below)
 //     P8 = e4m3(P * sv / sv_max * 16)          the key block's V scale is folded into the probabilities
 //     O  = (P8 v8) * sv_max / 16 / sum(P)      fp32 accumulation, bf16 result
 // Both products use v_mfma_f32_32x32x64_f8f6f4 (64-deep contraction, twice the bf16 rate), transposed as in the bf16
-// kernel (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query.  A workgroup is 4 wavefronts x 32 queries = one
-// 128-position scale block of queries; keys are walked in tiles of 64, which never straddle a scale block.
+// kernel (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query.  A workgroup is 8 wavefronts x 32 queries; a
+// wavefront's queries lie inside one 128-position scale block; keys are walked in tiles of 64, which never straddle one.
 //   * The probabilities leave the accumulators as 16 values per 32-key block in the accumulator's key order (4h..4h+3,
 //     8+4h..); packed to bytes, one v_permlane32_swap per 16 keys turns that into 8 consecutive keys per lane half,
 //     which is the order ds_read_b64_tr_b8 (transposing LDS read for bytes) delivers V^T in.
@@ -28,8 +29,9 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
 constexpr int KT8 = 64;            // keys per tile = contraction depth of one PV MFMA
-constexpr float GROW_LOG2 = 4.0f;  // lazy reference update threshold: probabilities stay below 2^4
-constexpr float P_GAIN = 16.0f;    // probabilities are multiplied by (sv / sv_max) * 16 before the E4M3 cast: at most 256 < 448
+constexpr int NW8 = 8;             // wavefronts per workgroup: 256 queries (two scale blocks) share each K/V tile
+constexpr int NT8 = 64 * NW8;
+constexpr float P_GAIN = 16.0f;    // probabilities are multiplied by (sv / sv_max) * 16 before the E4M3 cast
 
 __device__ inline void lane_pair_f(float x, float& lo, float& hi) {
     const unsigned a = __float_as_uint(x);
@@ -40,15 +42,17 @@ __device__ inline void lane_pair_f(float x, float& lo, float& hi) {
 }
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
+__global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
     constexpr int NJ = D / 64;         // 64-channel MFMA steps of S^T = K Q^T
     constexpr int MT = D / 32;         // 32-channel blocks of O^T
     constexpr int K_STRIDE = D + 16;   // bytes
     constexpr int V_STRIDE = D + 32;
     constexpr int K_BYTES = KT8 * K_STRIDE, V_BYTES = KT8 * V_STRIDE;
-    constexpr int CPT = D / 64;        // 16-byte chunks per staging thread (4 threads per row)
+    constexpr int CH = D / 16;         // 16-byte chunks per row
+    constexpr int TPR = (NT8 / KT8 < CH) ? NT8 / KT8 : CH;  // threads that stage one row of a tile
+    constexpr int CPT = CH / TPR;      // 16-byte chunks per staging thread
     __shared__ __attribute__((aligned(16))) char lds[2 * K_BYTES + 2 * V_BYTES];
-    __shared__ float sv_part[4];
+    __shared__ float sv_part[NW8];
     char* const lds_k = lds;
     char* const lds_v = lds + 2 * K_BYTES;
 
@@ -70,30 +74,36 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uin
 
     // largest V scale of the unit: the probabilities carry sv / sv_max, the output is multiplied by sv_max at the end
     float svm = 0.f;
-    for (uint32_t i = tid; i < n_blk; i += 256) svm = fmaxf(svm, svp[i]);
+    for (uint32_t i = tid; i < n_blk; i += NT8) svm = fmaxf(svm, svp[i]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) svm = fmaxf(svm, __shfl_xor(svm, off));
     if (lane == 0) sv_part[wave] = svm;
     __syncthreads();
-    const float sv_max = fmaxf(fmaxf(sv_part[0], sv_part[1]), fmaxf(sv_part[2], sv_part[3]));
+    float sv_max = sv_part[0];
+#pragma unroll
+    for (int i = 1; i < NW8; i++) sv_max = fmaxf(sv_max, sv_part[i]);
     const float p_gain = P_GAIN / sv_max;
 
     // Q fragments: lane = query lq, 32 consecutive channels starting at 64*j + 32*h
-    const uint32_t jq = qt * 128u + wave * 32u + lq;
+    const uint32_t jq = qt * (32u * NW8) + wave * 32u + lq;
     const bool q_valid = jq < n_seq;
     const size_t q_off = (size_t)(q_valid ? jq : n_seq - 1u) * C;
     i32x8 qf[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; j++) qf[j] = *(const i32x8*)(Qg + q_off + 64 * j + 32 * h);
-    const float cq = a.scale * 1.4426950408889634f * a.sq[(size_t)unit * n_blk + qt];  // the workgroup's queries are one scale block
+    // a wavefront's 32 queries lie inside one 128-position scale block (clamped for wavefronts past the end)
+    const uint32_t q_blk = (qt * (32u * NW8) + wave * 32u) / 128u;
+    const float cq = a.scale * 1.4426950408889634f * a.sq[(size_t)unit * n_blk + (q_blk < n_blk ? q_blk : n_blk - 1u)];
 
-    // staging: 4 threads per row of a 64-key tile, CPT consecutive 16-byte chunks each
-    const uint32_t st_row = tid >> 2, st_piece = tid & 3u;
+    // staging: TPR threads per row of a 64-key tile, CPT consecutive 16-byte chunks each
+    const uint32_t st_row = (tid / TPR) % KT8, st_piece = tid % TPR;
+    const bool st_active = tid < KT8 * TPR;  // with short rows only part of the workgroup stages
     u32x4 kreg[CPT], vreg[CPT];
     auto load_tile = [&](uint32_t t) {
         uint32_t j = t * KT8 + st_row;
         j = j < n_seq ? j : n_seq - 1u;
         const size_t off = (size_t)j * C + (st_piece * CPT) * 16;
+        if (!st_active) return;
 #pragma unroll
         for (int i = 0; i < CPT; i++) {
             kreg[i] = *(const u32x4*)(Kg + off + i * 16);
@@ -101,6 +111,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uin
         }
     };
     auto store_tile = [&](uint32_t buf) {
+        if (!st_active) return;
 #pragma unroll
         for (int i = 0; i < CPT; i++) {
             *(u32x4*)(lds_k + buf * K_BYTES + st_row * K_STRIDE + (st_piece * CPT + i) * 16) = kreg[i];
@@ -154,47 +165,60 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uin
                     sacc[kt][r] = key < n_seq ? sacc[kt][r] : -INFINITY;
                 }
         }
-        // online softmax
-        float mx = sacc[0][0];
+        // Online softmax without a per-tile maximum.  The exponentials are taken against the reference the row already
+        // has, with log2 of the tile's probability gain folded into the exponent, so one fma and one exp per key give
+        // P * gain directly.  Guard: E4M3 has no infinity and the conversion returns NaN above 448, so if a lane's 32
+        // scaled probabilities add up to 448 or more (always on the first tile, where the reference is -inf) the
+        // wavefront takes the rare path: true maximum, reference raised, tile redone.
+        const float lg = __builtin_amdgcn_logf(pg);   // log2 of the gain of this key block
+        const float inv_pg = __builtin_amdgcn_rcpf(pg);
+        auto probs = [&](float mref_eff, i32x8& dst) -> float {
+            float lsum = 0.f;
 #pragma unroll
-        for (int kt = 0; kt < 2; kt++)
+            for (int kt = 0; kt < 2; kt++) {
+                int w[4];  // dword i of the block: keys 8*i + 4*h + 0..3
 #pragma unroll
-            for (int r = 0; r < 16; r++) mx = fmaxf(mx, sacc[kt][r]);
-        float lo, hi;
-        lane_pair_f(mx, lo, hi);
-        const float m_new = fmaxf(m_ref, fmaxf(lo, hi) * ct);
-        const bool grow = m_new - m_ref > GROW_LOG2;  // same in lanes l and l^32
-        const bool any_grow = __builtin_amdgcn_ballot_w64(grow) != 0;
-        const float m_use = grow ? m_new : m_ref;
-        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_use);  // 1 where the reference stays, 0 on the first tile
-        m_ref = m_use;
-        float lsum = 0.f;
-        i32x8 pb;  // B operand of O^T += V^T P^T: 32 byte slots per lane half, slot 8*g16 + e <-> key 16*g16 + 8*h + e
+                for (int i = 0; i < 4; i++) {
+                    float pe[4];
 #pragma unroll
-        for (int kt = 0; kt < 2; kt++) {
-            int w[4];  // dword i of the block: keys 8*i + 4*h + 0..3
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                float pe[4];
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    pe[e] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][4 * i + e], ct, -m_use));
-                    lsum += pe[e];
+                    for (int e = 0; e < 4; e++) {
+                        pe[e] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][4 * i + e], ct, -mref_eff));
+                        lsum += pe[e];
+                    }
+                    const int pk = __builtin_amdgcn_cvt_pk_fp8_f32(pe[0], pe[1], 0, false);
+                    w[i] = __builtin_amdgcn_cvt_pk_fp8_f32(pe[2], pe[3], pk, true);
                 }
-                int pk = __builtin_amdgcn_cvt_pk_fp8_f32(pe[0] * pg, pe[1] * pg, 0, false);
-                w[i] = __builtin_amdgcn_cvt_pk_fp8_f32(pe[2] * pg, pe[3] * pg, pk, true);
-            }
 #pragma unroll
-            for (int m2 = 0; m2 < 2; m2++) {
-                // lanes l / l^32 hold keys (4h.., 8+4h..) of the 16-key group; after the swap each holds 8 consecutive keys
-                const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)w[2 * m2], (unsigned)w[2 * m2 + 1], false, false);
-                const unsigned s0 = sw[0], s1 = sw[1];
-                pb[(kt * 2 + m2) * 2] = (int)s0;
-                pb[(kt * 2 + m2) * 2 + 1] = (int)s1;
+                for (int m2 = 0; m2 < 2; m2++) {
+                    // lanes l / l^32 hold keys (4h.., 8+4h..) of the 16-key group; after the swap each holds 8 consecutive keys
+                    const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)w[2 * m2], (unsigned)w[2 * m2 + 1], false, false);
+                    const unsigned s0 = sw[0], s1 = sw[1];
+                    dst[(kt * 2 + m2) * 2] = (int)s0;
+                    dst[(kt * 2 + m2) * 2 + 1] = (int)s1;
+                }
             }
+            return lsum;
+        };
+        i32x8 pb;  // B operand of O^T += V^T P^T: 32 byte slots per lane half, slot 8*g16 + e <-> key 16*g16 + 8*h + e
+        float lsum = probs(m_ref - lg, pb);
+        float alpha = 1.0f;
+        bool rescale = false;  // wave-uniform
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(lsum < 448.0f)) != 0, 0)) {
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) mx = fmaxf(mx, sacc[kt][r]);
+            float lo, hi;
+            lane_pair_f(mx, lo, hi);
+            const float m_new = fmaxf(m_ref, fmaxf(lo, hi) * ct);
+            alpha = __builtin_amdgcn_exp2f(m_ref - m_new);  // 0 on the first tile
+            m_ref = m_new;
+            lsum = probs(m_ref - lg, pb);  // now every probability is at most the gain (<= 16)
+            rescale = true;
         }
-        l_run = fmaf(l_run, alpha, lsum);
-        if (any_grow) {
+        l_run = fmaf(l_run, alpha, lsum * inv_pg);
+        if (__builtin_expect(rescale, 0)) {  // a block of its own: nothing but the in-place multiplies
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
 #pragma unroll
@@ -241,10 +265,10 @@ template <int D>
 static hipError_t launch_fp8_t(const Fp8AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
-    const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 127u) / 128u;
+    const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 32u * NW8 - 1u) / (32u * NW8);
     const uint64_t blocks = (uint64_t)((n_units + 7u) / 8u * 8u) * q_tiles;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    attn_fwd_fp8_kernel<D><<<(uint32_t)blocks, 256, 0, stream>>>(a, q_tiles, n_units);
+    attn_fwd_fp8_kernel<D><<<(uint32_t)blocks, NT8, 0, stream>>>(a, q_tiles, n_units);
     return hipGetLastError();
 }
 
