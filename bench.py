@@ -54,8 +54,9 @@ def main() -> int:
     ap.add_argument("--workload", default="768p", choices=["480p", "768p"])
     ap.add_argument("--cpu-rows", type=int, default=16384, help="query rows the oracle computes for cpu_baseline")
     ap.add_argument("--skip-extras", action="store_true", help="only the headline timing (used under the profiler)")
-    ap.add_argument("--extras", default="group,unfused,permute,dense,fp8,cpu",
-                    help="comma list of the extra sections to run: group, unfused, permute, dense, fp8, cpu (oracle baseline + parity)")
+    ap.add_argument("--extras", default="group,unfused,permute,dense,fp8,pad,cpu",
+                    help="comma list of the extra sections to run: group, unfused, permute, dense, fp8, pad (720P-shaped grid in the "
+                         "any-resolution mode), cpu (oracle baseline + parity)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -181,6 +182,24 @@ def main() -> int:
         extras["fp8_speedup_vs_bf16"] = round(ms / f8_ms, 3)
         out8 = out.clone()
         del q8, k8, v8
+    if "pad" in sections and w.name == "768p":
+        # any-resolution mode on the paper's padded workload: 81 x 720 x 1280 video -> grid 21 x 45 x 80, padded to 21 x 48 x 80
+        Hp_real = 45
+        g = torch.Generator(device="cuda").manual_seed(5)
+        shp = (w.B, T * Hp_real * W, w.heads, w.D)
+        qp, kp, vp = (torch.randn(shp, generator=g, device="cuda", dtype=torch.bfloat16) for _ in range(3))
+        op = torch.empty_like(qp)
+        pad_ms = time_calls(lambda: sk.skiparse_attn_fwd(qp, kp, vp, T, Hp_real, W, s, "token", scale=w.scale, fused=True, pad=True, out=op), it, 1)
+        # real work: every class holds the real rows h = p, p+2, ... < 45 and all 40 columns of its parity
+        real_flops = 0.0
+        for p_ in range(s):
+            rows_c = len(range(p_, Hp_real, s))
+            for q_ in range(s):
+                n_c = T * rows_c * len(range(q_, W, s))
+                real_flops += 4.0 * w.B * w.heads * float(n_c) ** 2 * w.D
+        extras["pad720p_token_ms"] = round(pad_ms, 4)
+        extras["pad720p_real_tflops"] = round(real_flops / pad_ms / 1e9, 2)
+        del qp, kp, vp, op
     if extras:
         result["extras"] = extras
 

@@ -32,7 +32,7 @@ extern "C" {
 
 enum { SKIPARSE_TOKEN = 0, SKIPARSE_GROUP = 1 };                       /* pattern */
 enum { SKIPARSE_BF16 = 0, SKIPARSE_FP32 = 1, SKIPARSE_FP8_E4M3 = 2 };  /* element type of a tensor */
-enum { SKIPARSE_FUSED = 1u };                                          /* flags of skiparse_attn_fwd */
+enum { SKIPARSE_FUSED = 1u, SKIPARSE_PAD = 2u };                       /* flags of skiparse_attn_fwd */
 
 enum {
     SKIPARSE_OK = 0,
@@ -73,6 +73,11 @@ int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B
  *   flags = SKIPARSE_FUSED one kernel that computes each row's address from (subsequence, position); no
  *                          permuted copy is written and no workspace is needed (workspace may be NULL).
  * Both give the same result up to fp32 summation order.
+ *   flags = SKIPARSE_FUSED | SKIPARSE_PAD   any-resolution mode (Sec. 3.2): H and W may be arbitrary; the grid is treated as
+ *                          padded at the END of H and W to the next multiples of s*s, padding positions are masked as keys
+ *                          and skipped as queries.  q, k, v, out still hold only the T*H*W real tokens; no padded copy is
+ *                          made (the padding is an address predicate of the fused kernel).  Without SKIPARSE_FUSED the
+ *                          flag is rejected with SKIPARSE_EUNSUPPORTED.
  */
 int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
                       int head_dim, int s, int pattern, float scale, int dtype, unsigned flags, void* workspace,

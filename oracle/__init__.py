@@ -56,6 +56,8 @@ def _load():
         lib.oracle_skiparse_attention.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, dbl, i]
         lib.oracle_skiparse_attention_rows.restype = i
         lib.oracle_skiparse_attention_rows.argtypes = [vp, vp, vp, vp, i64, vp, i, i, i, i, i, i, i, i, dbl, i]
+        lib.oracle_skiparse_attention_rows_padded.restype = i
+        lib.oracle_skiparse_attention_rows_padded.argtypes = [vp, vp, vp, vp, i64, vp, i, i, i, i, i, i, i, i, dbl, i]
         lib.oracle_masked_dense_attention.restype = i
         lib.oracle_masked_dense_attention.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, dbl, i]
         lib.oracle_quantize_fp8.restype = i
@@ -219,3 +221,22 @@ def quantize_fp8(x: np.ndarray, T: int, H: int, W: int, s: int, pattern: str):
     scales = np.empty((s * s * B, heads, (nsub + 127) // 128), dtype=np.float32)
     _check(_load().oracle_quantize_fp8(_ptr(x), _ptr(x8), _ptr(scales), B, heads, T, H, W, D, s, PATTERNS[pattern]), "quantize_fp8")
     return x8, scales
+
+
+def skiparse_attention_rows_padded(q, k, v, rows, T: int, H: int, W: int, s: int, pattern: str, scale: float) -> np.ndarray:
+    """Any-resolution Skiparse attention (end padding to multiples of s*s, padding masked), rows[i] = (b, head, n) only.
+    H and W need not be divisible by anything; for divisible grids this equals skiparse_attention_rows."""
+    code = _dtype_code(q, k, v)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
+    out = np.empty((rows.shape[0], D), dtype=np.float64)
+    _check(
+        _load().oracle_skiparse_attention_rows_padded(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(rows), rows.shape[0], _ptr(out), B, heads, T, H, W, D, s,
+            PATTERNS[pattern], float(scale), code,
+        ),
+        "skiparse_attention_rows_padded",
+    )
+    return out

@@ -269,15 +269,76 @@ int oracle_skiparse_attention_rows(const void *q, const void *k, const void *v, 
 }
 
 /*
+ * Any-resolution variant (Sec. 3.2): when H or W is not a multiple of s*s the figure is padded at the END of both axes
+ * up to the next multiple and the padding tokens are masked out of the attention.  Padding at the end does not change the
+ * class of a real token (the class formulas of Sec. 3.1 only look at h and w), so the definition is: every real token
+ * attends to all REAL tokens of its own class and batch element.  Written in that mask form, with no padded copy and no
+ * position arithmetic; it needs no divisibility at all.  rows = [n_rows][3] (b, head, n), out = [n_rows][D].
+ */
+static void class_of(int pattern, int s, int H, int W, int64_t n, int *p, int *q)
+{
+    int64_t w = n % W, h = (n / W) % H;
+    if (pattern == ORACLE_TOKEN) {
+        *p = (int)(h % s);
+        *q = (int)(w % s);
+    } else {
+        *p = (int)((h / s) % s);
+        *q = (int)((w / s) % s);
+    }
+}
+
+int oracle_skiparse_attention_rows_padded(const void *q, const void *k, const void *v, const int64_t *rows, int64_t n_rows,
+                                          double *out, int B, int heads, int T, int H, int W, int D, int s, int pattern,
+                                          double scale, int dtype)
+{
+    if (!q || !k || !v || !rows || !out || n_rows < 0 || heads < 1 || D < 1) return -1;
+    if (B < 1 || T < 1 || H < 1 || W < 1 || s < 1 || (pattern != ORACLE_TOKEN && pattern != ORACLE_GROUP)) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W;
+    for (int64_t r = 0; r < n_rows; r++)
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= heads || rows[3 * r + 2] < 0 ||
+            rows[3 * r + 2] >= N)
+            return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *scores = (double *)malloc(sizeof(double) * (size_t)N);
+        int64_t *off = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);
+        if (!scores || !off) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t r = 0; r < n_rows; r++) {
+                int64_t b = rows[3 * r], hd = rows[3 * r + 1], n = rows[3 * r + 2];
+                int pn, qn, pm, qm;
+                class_of(pattern, s, H, W, n, &pn, &qn);
+                int64_t cnt = 0;
+                for (int64_t m = 0; m < N; m++) {
+                    class_of(pattern, s, H, W, m, &pm, &qm);
+                    if (pm == pn && qm == qn) off[cnt++] = (b * N + m) * C + hd * D;
+                }
+                attention_row(q, (b * N + n) * C + hd * D, k, v, off, cnt, D, scale, dtype, scores, out + r * D);
+            }
+        }
+        free(scores);
+        free(off);
+    }
+    return fail ? -2 : 0;
+}
+
+/*
  * Brute force for tiny grids (Sec. 3.1: a token interacts only with tokens of its own sub-figure):
  * full N x N attention in the original order where the logit of a pair is -inf unless both tokens
  * are in the same batch element and have the same (p,q) class.  Uses only the class of a token,
- * never its position j, and never a permuted copy.
+ * never its position j, and never a permuted copy; H and W need not be divisible (for grids that are
+ * not, this is the padded-and-masked attention of Sec. 3.2, since end padding leaves classes unchanged).
  */
 int oracle_masked_dense_attention(const void *q, const void *k, const void *v, double *out, int B, int heads, int T, int H, int W,
                                   int D, int s, int pattern, double scale, int dtype)
 {
-    if (!q || !k || !v || !out || heads < 1 || D < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    if (!q || !k || !v || !out || heads < 1 || D < 1 || B < 1 || T < 1 || H < 1 || W < 1 || s < 1) return -1;
+    if (pattern != ORACLE_TOKEN && pattern != ORACLE_GROUP) return -1;
     if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
     int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W;
     double *logit = (double *)malloc(sizeof(double) * (size_t)N);
@@ -286,12 +347,11 @@ int oracle_masked_dense_attention(const void *q, const void *k, const void *v, d
         for (int hd = 0; hd < heads; hd++)
             for (int64_t n = 0; n < N; n++) {
                 int pn, qn, pm, qm;
-                int64_t jn, jm;
                 int64_t qo = (b * N + n) * C + (int64_t)hd * D;
-                oracle_dst_index(pattern, s, T, H, W, n, &pn, &qn, &jn);
+                class_of(pattern, s, H, W, n, &pn, &qn);
                 double m = -INFINITY;
                 for (int64_t mm = 0; mm < N; mm++) {
-                    oracle_dst_index(pattern, s, T, H, W, mm, &pm, &qm, &jm);
+                    class_of(pattern, s, H, W, mm, &pm, &qm);
                     if (pm != pn || qm != qn) {
                         logit[mm] = -INFINITY;
                         continue;

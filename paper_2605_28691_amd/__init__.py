@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libskiparse.so")
 TOKEN, GROUP = 0, 1
 BF16, FP32, FP8_E4M3 = 0, 1, 2
 FUSED = 1
+PAD = 2
 PATTERNS = {"token": TOKEN, "group": GROUP}
 _DTYPES = {torch.bfloat16: BF16, torch.float32: FP32, torch.uint8: FP8_E4M3, torch.float8_e4m3fn: FP8_E4M3}
 
@@ -130,9 +131,10 @@ def skiparse_workspace_bytes(B, heads, T, H, W, D, s, fused: bool) -> int:
 
 
 def skiparse_attn_fwd(q, k, v, T: int, H: int, W: int, s: int, pattern: str, scale: float = 0.0, fused: bool = True,
-                      out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+                      out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, pad: bool = False):
     """Skiparse-2D attention, q/k/v/out in the original layout.  The unfused path needs a uint8 device workspace of
-    skiparse_workspace_bytes() bytes; one is allocated with torch if none is passed."""
+    skiparse_workspace_bytes() bytes; one is allocated with torch if none is passed.  pad=True selects the any-resolution
+    mode (fused only): H and W arbitrary, end padding to multiples of s*s masked."""
     B, heads, D = _dims(q, T, H, W)
     if out is None:
         out = torch.empty_like(q)
@@ -144,7 +146,7 @@ def skiparse_attn_fwd(q, k, v, T: int, H: int, W: int, s: int, pattern: str, sca
         ws_ptr, ws_bytes = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
     _check(
         lib().skiparse_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), B, heads, T, H, W, D, s,
-                                PATTERNS[pattern], float(scale), _DTYPES[q.dtype], FUSED if fused else 0, ws_ptr, ws_bytes,
+                                PATTERNS[pattern], float(scale), _DTYPES[q.dtype], (FUSED if fused else 0) | (PAD if pad else 0), ws_ptr, ws_bytes,
                                 _stream()),
         "skiparse_attn_fwd",
     )

@@ -38,17 +38,22 @@ struct Shape {
 };
 
 // Checks everything that does not involve pointers.  Returns SKIPARSE_OK and fills `sh`, or an error code.
-int check_shape(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, Shape* sh) {
+int check_shape(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, Shape* sh, bool allow_pad = false) {
     if (B < 1 || heads < 1 || T < 1 || H < 1 || W < 1 || head_dim < 1 || s < 1) return SKIPARSE_EINVAL;
     if (pattern != SKIPARSE_TOKEN && pattern != SKIPARSE_GROUP) return SKIPARSE_EINVAL;
     if (s > 1024) return SKIPARSE_ESHAPE;
     const int unit = pattern == SKIPARSE_TOKEN ? s : s * s;
-    if (H % unit != 0 || W % unit != 0) return SKIPARSE_ESHAPE;
+    if (!allow_pad && (H % unit != 0 || W % unit != 0)) return SKIPARSE_ESHAPE;
     const uint64_t n_tok = (uint64_t)T * (uint64_t)H * (uint64_t)W;
     const uint64_t rows = n_tok * (uint64_t)B;
     if (rows >= (1ull << 31)) return SKIPARSE_ESHAPE;  // row numbers are 32-bit in the kernels
-    const uint64_t n_sub = n_tok / ((uint64_t)s * s);
-    const uint64_t dmax = (uint64_t)(W / s) > (uint64_t)s ? (uint64_t)(W / s) : (uint64_t)s;
+    // in the any-resolution mode the subsequences are those of the grid padded to multiples of s*s
+    const uint64_t Hp = allow_pad ? ((uint64_t)H + s * s - 1) / (s * s) * (s * s) : (uint64_t)H;
+    const uint64_t Wp = allow_pad ? ((uint64_t)W + s * s - 1) / (s * s) * (s * s) : (uint64_t)W;
+    if ((uint64_t)T * Hp * Wp >= (1ull << 31)) return SKIPARSE_ESHAPE;
+    const uint64_t n_sub = (uint64_t)T * Hp * Wp / ((uint64_t)s * s);
+    uint64_t dmax = Wp / (uint64_t)s > (uint64_t)s ? Wp / (uint64_t)s : (uint64_t)s;
+    if (allow_pad && Hp > dmax) dmax = Hp;
     if (n_sub * dmax >= (1ull << 32)) return SKIPARSE_ESHAPE;  // range of the multiply-high divisions
     const uint64_t row_elems = (uint64_t)heads * (uint64_t)head_dim;
     if (row_elems >= (1ull << 31) || rows * row_elems >= (1ull << 40)) return SKIPARSE_ESHAPE;
@@ -72,26 +77,32 @@ GridMap make_dense_gridmap(size_t n) {
     g.ws = make_fastdiv(0xffffffffu);  // multiplier 2: the quotient is 0 for every position below 2^31
     g.step_r = 0;
     g.step_w = 64;
+    g.H_real = 1;
+    g.hpad = make_fastdiv(1);
     g.sdiv = make_fastdiv(1);
     return g;
 }
 
-GridMap make_gridmap(int T, int H, int W, int s, int pattern) {
+GridMap make_gridmap(int T, int H, int W, int s, int pattern, bool pad = false) {
     const int n_tok = T * H * W;
     if (s == 1) return make_dense_gridmap((size_t)n_tok);
+    const int Hp = pad ? (H + s * s - 1) / (s * s) * (s * s) : H;
+    const int Wp = pad ? (W + s * s - 1) / (s * s) * (s * s) : W;
     GridMap g;
     g.mode = pattern == SKIPARSE_TOKEN ? MODE_TOKEN : MODE_GROUP;
     g.s = s;
     g.W = W;
     g.n_tok = n_tok;
-    g.n_sub = n_tok / (s * s);
+    g.n_sub = T * Hp * Wp / (s * s);
     g.a = pattern == SKIPARSE_TOKEN ? (uint32_t)s : 1u;
     g.b = pattern == SKIPARSE_TOKEN ? 0u : (uint32_t)(s * s - s);
     g.cmul = pattern == SKIPARSE_TOKEN ? 1u : (uint32_t)s;
-    g.ws = make_fastdiv((uint32_t)(W / s));
+    g.ws = make_fastdiv((uint32_t)(Wp / s));
     g.sdiv = make_fastdiv((uint32_t)s);
-    g.step_r = 64u / (uint32_t)(W / s);
-    g.step_w = 64u % (uint32_t)(W / s);
+    g.step_r = 64u / (uint32_t)(Wp / s);
+    g.step_w = 64u % (uint32_t)(Wp / s);
+    g.H_real = H;
+    g.hpad = make_fastdiv((uint32_t)Hp);
     return g;
 }
 
@@ -166,6 +177,7 @@ int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B
     a.B = B; a.heads = heads; a.head_dim = head_dim;
     a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
     a.g = make_dense_gridmap(sh.n_tok);
+    a.pad = false;
     return finish(launch_attn_bf16(a, (hipStream_t)stream));
 }
 
@@ -179,10 +191,13 @@ size_t skiparse_workspace_bytes(int B, int heads, int T, int H, int W, int head_
 int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
                       int head_dim, int s, int pattern, float scale, int dtype, unsigned flags, void* workspace,
                       size_t workspace_bytes, void* stream) {
+    if (flags & ~(unsigned)(SKIPARSE_FUSED | SKIPARSE_PAD)) return SKIPARSE_EINVAL;
+    const bool pad = (flags & SKIPARSE_PAD) != 0 && s > 1;
     Shape sh;
-    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh, pad);
     if (rc != SKIPARSE_OK) return rc;
-    if (elem_size(dtype) == 0 || (flags & ~(unsigned)SKIPARSE_FUSED)) return SKIPARSE_EINVAL;
+    if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
+    if (pad && !(flags & SKIPARSE_FUSED)) return SKIPARSE_EUNSUPPORTED;  // padding exists only as an address predicate of the fused kernel
     if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
     const size_t bytes = sh.elems * 2;
     rc = check_attn_ranges(sh, W, 2);
@@ -195,7 +210,8 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
     hipStream_t st = (hipStream_t)stream;
     if (flags & SKIPARSE_FUSED) {
         a.q = q; a.k = k; a.v = v; a.out = out;
-        a.g = make_gridmap(T, H, W, s, pattern);
+        a.g = make_gridmap(T, H, W, s, pattern, pad);
+        a.pad = pad;
         return finish(launch_attn_bf16(a, st));
     }
     const size_t need = 4 * align256(bytes);
@@ -217,6 +233,7 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
     a.q = qp; a.k = kp; a.v = vp; a.out = op;
     a.B = B * s * s;  // the subsequences are the batch of the inner attention (Alg. 1: "(p q b)")
     a.g = make_dense_gridmap(sh.n_sub);
+    a.pad = false;
     if ((e = launch_attn_bf16(a, st)) != hipSuccess) return finish(e);
     return finish(launch_permute(op, out, B, g, row_bytes, 0, st));
 }

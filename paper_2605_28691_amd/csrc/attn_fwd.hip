@@ -95,13 +95,16 @@ __device__ inline size_t uniform(size_t x) {
 }
 
 // GROUP selects the group-wise index map (two extra divisions by s per staged row); token-wise and dense use GROUP = false.
-template <int D, int QT, bool GROUP>
+// PAD selects the any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s, padding positions
+// are masked as keys (a validity byte per staged row in LDS) and skipped as queries; every block takes the masked step.
+template <int D, int QT, bool GROUP, bool PAD>
 __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
     using TL = Tile<D>;
     constexpr int KS = D / 16;     // MFMA steps along head_dim for S^T = K Q^T
     constexpr int MT = D / 32;     // 32-row blocks of O^T
     constexpr int BR = 32 * NW * QT;   // query rows per workgroup: QT tiles of 32 per wavefront
     __shared__ __attribute__((aligned(16))) char lds[2 * TL::K_BYTES + 2 * TL::V_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char kmask[4][KT];  // PAD only: 1 = real key, per row of the last 4 K tiles
     char* const lds_k = lds;
     char* const lds_v = lds + 2 * TL::K_BYTES;
 
@@ -137,7 +140,14 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     for (int qi = 0; qi < QT; qi++) {
         const uint32_t jq = qt * BR + (wave * QT + qi) * 32u + lq;
         q_valid[qi] = jq < n_seq;
-        q_row_off[qi] = (size_t)src_token(a.g, p, q, q_valid[qi] ? jq : n_seq - 1u) * C;
+        if (PAD) {
+            bool real;
+            const uint32_t tok = src_token_padded(a.g, p, q, q_valid[qi] ? jq : 0u, &real);
+            q_valid[qi] = q_valid[qi] && real;
+            q_row_off[qi] = q_valid[qi] ? (size_t)tok * C : 0;  // padding queries read token 0 and store nothing
+        } else {
+            q_row_off[qi] = (size_t)src_token(a.g, p, q, q_valid[qi] ? jq : n_seq - 1u) * C;
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) qf[qi][ks] = *(const bf16x8*)(Qg + q_row_off[qi] + ks * 16 + 8 * h);
     }
@@ -150,11 +160,18 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     // Tiles are visited in order, so (r, ws) = (j / Ws, j % Ws) of the row are advanced by 64 positions with adds and one
     // wrap instead of being divided out again; the products use 24-bit multiplies (operands checked on the host).
     const uint32_t Ws = a.g.ws.d, row_bytes = (uint32_t)C * 2u;
-    const uint32_t last_off = src_token(a.g, p, q, n_seq - 1u) * row_bytes;  // rows past the end read the last valid row
+    const uint32_t last_off = PAD ? 0u : src_token(a.g, p, q, n_seq - 1u) * row_bytes;  // rows past the end read the last valid row
+    bool cur_valid = true, kreg_valid = true;  // PAD: whether the row whose offset was formed last / the row held in kreg is a real token
     uint32_t st_r = a.g.ws.div(st_row), st_ws = st_row - st_r * Ws;  // position of tile 0's row (st_row < 64 <= any range limit)
     uint32_t st_j = st_row;
     const uint32_t row_c = p * a.g.cmul, col_c = q * a.g.cmul;
     auto row_off_now = [&]() -> uint32_t {
+        if (PAD) {  // positions are divided out again: the padded variant is not the fast path
+            bool real;
+            const uint32_t tok = src_token_padded(a.g, p, q, st_j < n_seq ? st_j : 0u, &real);
+            cur_valid = real && st_j < n_seq;
+            return cur_valid ? tok * row_bytes : 0u;  // padding rows read token 0; their logits are masked
+        }
         uint32_t row = mad24(st_r, a.g.a, row_c);
         uint32_t w = mad24(st_ws, a.g.a, col_c);
         if (GROUP) {
@@ -177,6 +194,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         return row_off_now();
     };
     auto load_k = [&](uint32_t off) {
+        kreg_valid = cur_valid;
 #pragma unroll
         for (int i = 0; i < TL::CPT; i++)
             kreg[i] = *(const u32x4*)((const char*)Kg + off + (st_piece * TL::CPT + i) * 16);
@@ -185,7 +203,9 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
 #pragma unroll
         for (int i = 0; i < TL::CPT; i++) vreg[i] = *(const u32x4*)((const char*)Vg + off + (st_piece + TL::TPR * i) * 16);
     };
-    auto store_k = [&](uint32_t buf) {
+    auto store_k = [&](uint32_t tile) {
+        const uint32_t buf = tile & 1u;
+        if (PAD && st_piece == 0) kmask[tile & 3u][st_row] = kreg_valid ? 1 : 0;
 #pragma unroll
         for (int i = 0; i < TL::CPT; i++)
             *(u32x4*)(lds_k + buf * TL::K_BYTES + st_row * TL::K_STRIDE + (st_piece * TL::CPT + i) * 16) = kreg[i];
@@ -301,10 +321,19 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         for (int qi = 0; qi < QT; qi++) {
             f32x16& s = sreg[PAR][qi];
             if (decltype(MASK)::value) {
+                if (PAD) {
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const uint32_t key = blk * 32u + 8 * (r >> 2) + 4 * h + (r & 3);
-                    s[r] = key < n_seq ? s[r] : -INFINITY;
+                    for (int i = 0; i < 4; i++) {  // keys 8*i + 4*h + 0..3 of the block: one dword of validity bytes
+                        const uint32_t m4 = *(const uint32_t*)&kmask[(blk >> 1) & 3u][(blk & 1u) * 32u + 8 * i + 4 * h];
+#pragma unroll
+                        for (int e = 0; e < 4; e++) s[4 * i + e] = ((m4 >> (8 * e)) & 1u) ? s[4 * i + e] : -INFINITY;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const uint32_t key = blk * 32u + 8 * (r >> 2) + 4 * h + (r & 3);
+                        s[r] = key < n_seq ? s[r] : -INFINITY;
+                    }
                 }
             }
             const float mx = fmaxf(max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8])),
@@ -315,9 +344,12 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
             const bool grow = (m_new - m_ref[qi]) * c > RESCALE_LOG2;  // same in lanes l and l^32
             grow_mask |= __builtin_amdgcn_ballot_w64(grow);
             const float m_use = grow ? m_new : m_ref[qi];
-            alpha_pending[qi] = __builtin_amdgcn_exp2f((m_ref[qi] - m_use) * c);  // 1 where the reference stays, 0 on the first block
+            // 1 where the reference stays (also while it is still -inf: a block of nothing but masked keys), 0 on the first real block
+            alpha_pending[qi] = grow ? __builtin_amdgcn_exp2f((m_ref[qi] - m_use) * c) : 1.0f;
             m_ref[qi] = m_use;
-            l_run[qi] = fmaf(l_run[qi], alpha_pending[qi], exps(s, m_use * c, preg[PAR][qi]));
+            // while no real key has been seen the reference is -inf: take 0 instead so that masked logits give exp2(-inf) = 0
+            const float mc_use = m_use == -INFINITY ? 0.f : m_use * c;
+            l_run[qi] = fmaf(l_run[qi], alpha_pending[qi], exps(s, mc_use, preg[PAR][qi]));
         }
         if (decltype(DO_PV)::value) pv(vb, PAR ^ 1, preg[PAR ^ 1]);
         pending = grow_mask != 0;  // O is rescaled at the start of the next step: after PV(b-1), before PV(b)
@@ -453,14 +485,19 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     for (; W + 1 < n_tiles; W++) {
         const char* kb = lds_k + (W & 1u) * TL::K_BYTES;
         const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
-        store_k((W + 1u) & 1u);       // K tile W+1
+        store_k(W + 1u);              // K tile W+1
         store_v(W & 1u);              // V tile W
         off_k = tile_row_off_next();  // tile W+2
         load_k(off_k);
         load_v(off_v);                // tile W+1
         off_v = off_k;
-        step_manual(P1{}, kb, vb);
-        step_manual(P0{}, kb, vb);
+        if (PAD) {  // every block takes the masked step
+            step(T_{}, T_{}, T_{}, P1{}, 2 * W - 1, kb, vb);
+            step(T_{}, T_{}, T_{}, P0{}, 2 * W, kb, vb);
+        } else {
+            step_manual(P1{}, kb, vb);
+            step_manual(P0{}, kb, vb);
+        }
         __syncthreads();
     }
     // ---- window n_tiles-1 (if there is more than one tile): the last K tile, may hold keys past the end
@@ -501,7 +538,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     }
 }
 
-template <int D, int QT, bool GROUP>
+template <int D, int QT, bool GROUP, bool PAD>
 static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
@@ -509,14 +546,20 @@ static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
     const uint32_t units_padded = (n_units + 7u) / 8u * 8u;
     const uint64_t blocks = (uint64_t)units_padded * q_tiles;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    attn_fwd_bf16_kernel<D, QT, GROUP><<<(uint32_t)blocks, NTHREADS, 0, stream>>>(a, q_tiles, n_units);
+    attn_fwd_bf16_kernel<D, QT, GROUP, PAD><<<(uint32_t)blocks, NTHREADS, 0, stream>>>(a, q_tiles, n_units);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
     const bool group = a.g.b != 0;
-    if (a.head_dim == 128) return group ? launch_t<128, ATTN_QT, true>(a, stream) : launch_t<128, ATTN_QT, false>(a, stream);
-    if (a.head_dim == 64) return group ? launch_t<64, ATTN_QT, true>(a, stream) : launch_t<64, ATTN_QT, false>(a, stream);
+    if (a.head_dim == 128) {
+        if (a.pad) return group ? launch_t<128, ATTN_QT, true, true>(a, stream) : launch_t<128, ATTN_QT, false, true>(a, stream);
+        return group ? launch_t<128, ATTN_QT, true, false>(a, stream) : launch_t<128, ATTN_QT, false, false>(a, stream);
+    }
+    if (a.head_dim == 64) {
+        if (a.pad) return group ? launch_t<64, ATTN_QT, true, true>(a, stream) : launch_t<64, ATTN_QT, false, true>(a, stream);
+        return group ? launch_t<64, ATTN_QT, true, false>(a, stream) : launch_t<64, ATTN_QT, false, false>(a, stream);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -55,6 +55,10 @@ struct GridMap {
     uint32_t step_r;  // 64 / (W/s) and 64 % (W/s): how (j / Ws, j % Ws) move when j advances by one 64-key tile
     uint32_t step_w;
     FastDiv sdiv;  // division by s
+    // Any-resolution mode (Sec. 3.2): positions enumerate the grid padded at the end of H and W to multiples of s*s;
+    // H_real rows of every H_pad are real, and columns below W (the real row length above) are real.
+    int H_real;
+    FastDiv hpad;  // division by the padded H
 };
 
 __host__ __device__ inline uint32_t src_token(const GridMap& g, uint32_t p, uint32_t q, uint32_t j) {
@@ -63,6 +67,20 @@ __host__ __device__ inline uint32_t src_token(const GridMap& g, uint32_t p, uint
     const uint32_t row = r * g.a + g.sdiv.div(r) * g.b + p * g.cmul;
     const uint32_t w = ws * g.a + g.sdiv.div(ws) * g.b + q * g.cmul;
     return row * (uint32_t)g.W + w;
+}
+
+// Any-resolution mode: position j of class (p, q) on the padded grid -> token number in the UNPADDED tensor and whether the
+// position is a real token.  g.ws divides by W_pad/s, g.hpad by H_pad; rows and columns of the padded grid come out of the
+// same affine forms as in src_token().
+__host__ __device__ inline uint32_t src_token_padded(const GridMap& g, uint32_t p, uint32_t q, uint32_t j, bool* real) {
+    const uint32_t r = g.ws.div(j);
+    const uint32_t ws = j - r * g.ws.d;
+    const uint32_t row = r * g.a + g.sdiv.div(r) * g.b + p * g.cmul;  // t * H_pad + h
+    const uint32_t w = ws * g.a + g.sdiv.div(ws) * g.b + q * g.cmul;
+    const uint32_t t = g.hpad.div(row);
+    const uint32_t h = row - t * g.hpad.d;
+    *real = h < (uint32_t)g.H_real && w < (uint32_t)g.W;
+    return (t * (uint32_t)g.H_real + h) * (uint32_t)g.W + w;
 }
 
 }  // namespace skiparse

@@ -25,6 +25,7 @@ struct AttnArgs {
     int heads;
     int head_dim;
     float scale;    // multiplies the logits
+    bool pad;       // any-resolution mode: g describes the padded grid, padding positions are masked / skipped
     GridMap g;
 };
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);

@@ -80,7 +80,11 @@ def test_attention_rejects_bad_arguments(lib):
         return lib.skiparse_attn_fwd(a[0], a[1], a[2], a[3], 1, 2, 2, H, 8, 64, s, pattern, f, 0, flags, ws, ws_bytes, None)
 
     assert sparse(1, None, 0, H=6, pattern=1) == -2
-    assert sparse(2, None, 0) == -1  # unknown flag bit
+    assert sparse(4, None, 0) == -1  # unknown flag bit
+    assert sparse(2, None, 0) == -3  # padding without the fused kernel
+    assert sparse(1, None, 0, H=7) == -2  # H = 7 needs the any-resolution flag
+    # with the flag the shape is accepted and the next check (out aliases q) is reached
+    assert lib.skiparse_attn_fwd(a[0], a[1], a[2], a[0], 1, 2, 2, 7, 9, 64, 2, 1, f, 0, 3, None, 0, None) == -1
     assert sparse(0, None, 0) == -4  # unfused path without a workspace
     need = lib.skiparse_workspace_bytes(1, 2, 2, 8, 8, 64, 2, 0, 0)
     assert need == 4 * 1 * 128 * 2 * 64 * 2

@@ -162,3 +162,52 @@ def test_768p_dense_sampled_rows():
     out = sk.dense_attn_fwd(*_gpu((q, k, v)), w.T, w.H, w.W, scale=w.scale)
     torch.cuda.synchronize()
     assert_close_bf16(gather_rows(out, rows), want, "dense 768p")
+
+
+PAD_CASES = [  # B, heads, D, T, H, W, s -- H or W not a multiple of s*s
+    (1, 2, 128, 3, 5, 7, 2),
+    (2, 3, 128, 4, 10, 13, 2),
+    (1, 2, 64, 5, 6, 30, 2),     # the 480P grid's H = 30 problem in small: 6 % 4 != 0
+    (1, 4, 128, 2, 11, 20, 3),
+    (1, 2, 128, 6, 8, 12, 2),    # divisible: the padded mode must agree with the plain one
+    (1, 1, 128, 9, 1, 33, 2),    # H = 1: the classes with p = 1 are empty
+]
+
+
+@pytest.mark.parametrize("B,heads,D,T,H,W,s", PAD_CASES)
+@pytest.mark.parametrize("pattern", ["token", "group"])
+def test_any_resolution_padding_small(B, heads, D, T, H, W, s, pattern):
+    """Any-resolution mode (end padding to multiples of s*s, padding masked) against the oracle's mask-form definition."""
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("pad", B, heads, D, T, H, W, s, seed=41 + s)
+    q, k, v = si.make_qkv(w)
+    rows = np.array([(b, hd, n) for b in range(B) for hd in range(heads) for n in range(T * H * W)], dtype=np.int64)
+    want = oracle.skiparse_attention_rows_padded(*oracle_inputs(q, k, v), rows, T, H, W, s, pattern, w.scale)
+    n = q.numel()
+    buf = torch.full((n + 4096,), 5.0, dtype=torch.bfloat16, device="cuda")
+    out = buf[2048 : 2048 + n].view(q.shape)
+    sk.skiparse_attn_fwd(*_gpu((q, k, v)), T, H, W, s, pattern, scale=w.scale, fused=True, pad=True, out=out)
+    torch.cuda.synchronize()
+    assert (buf[:2048] == 5.0).all() and (buf[2048 + n :] == 5.0).all()
+    assert_close_bf16(gather_rows(out, rows), want, f"padded {pattern}")
+    if H % (s * s) == 0 and W % (s * s) == 0:
+        plain = sk.skiparse_attn_fwd(*_gpu((q, k, v)), T, H, W, s, pattern, scale=w.scale, fused=True)
+        assert_close_bf16(to_np64(out), to_np64(plain), "padded vs plain")
+
+
+def test_any_resolution_720p_sampled_rows():
+    """The paper's padded workload: 81 x 720 x 1280 video, latent grid 21 x 45 x 80, padded to 21 x 48 x 80 (Tab. 2a),
+    40 heads of 128 channels, s = 2, both patterns: sampled rows against the oracle."""
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("720p", 1, 40, 128, 21, 45, 80, 2, seed=7)
+    q, k, v = si.make_qkv(w)
+    rows = si.sample_rows(w, 8, seed=7)
+    qd, kd, vd = _gpu((q, k, v))
+    for pattern in ("token", "group"):
+        want = oracle.skiparse_attention_rows_padded(*oracle_inputs(q, k, v), rows, w.T, w.H, w.W, w.s, pattern, w.scale)
+        out = sk.skiparse_attn_fwd(qd, kd, vd, w.T, w.H, w.W, w.s, pattern, scale=w.scale, fused=True, pad=True)
+        torch.cuda.synchronize()
+        assert_close_bf16(gather_rows(out, rows), want, f"720p {pattern}")
+        del out

@@ -150,3 +150,49 @@ def test_scale_enters_the_logits():
     q, k, v = (_rand((1, 12, 1, 4), i) for i in (41, 42, 43))
     assert np.allclose(oracle.attention(q, k, v, 0.8), oracle.attention(2 * q, k, v, 0.4), rtol=1e-12, atol=1e-14)
     assert not np.allclose(oracle.attention(q, k, v, 0.8), oracle.attention(q, k, v, 0.4))
+
+
+def _all_rows(B, heads, N):
+    return np.array([(b, h, n) for b in range(B) for h in range(heads) for n in range(N)], dtype=np.int64)
+
+
+@pytest.mark.parametrize("pattern", ["token", "group"])
+def test_padded_variant_reduces_to_plain_on_divisible_grids(pattern):
+    """Sec. 3.2: no mask is needed when H and W are multiples of s*s, so the padded variant must equal the plain one."""
+    B, heads, D, T, H, W, s = 2, 2, 8, 2, 8, 12, 2
+    q, k, v = (_rand((B, T * H * W, heads, D), i) for i in (51, 52, 53))
+    rows = _all_rows(B, heads, T * H * W)
+    a = oracle.skiparse_attention_rows_padded(q, k, v, rows, T, H, W, s, pattern, 0.3)
+    b = oracle.skiparse_attention_rows(q, k, v, rows, T, H, W, s, pattern, 0.3)
+    assert np.allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("pattern", ["token", "group"])
+@pytest.mark.parametrize("H,W,s", [(5, 7, 2), (3, 9, 2), (10, 11, 3), (1, 6, 2)])
+def test_padded_variant_equals_explicit_padding(pattern, H, W, s):
+    """Sec. 3.2 done literally: pad H and W at the end to multiples of s*s with zeros, run the divisible-grid attention on
+    the padded figure with the padding keys removed from every softmax (here by giving them a logit of about -1e9 through
+    an extra channel), and drop the padded queries.  Must equal the mask-form definition."""
+    B, heads, D, T = 1, 2, 6, 2
+    u = s * s
+    Hp, Wp = -(-H // u) * u, -(-W // u) * u
+    rng = np.random.default_rng(3)
+    q, k, v = (rng.standard_normal((B, T * H * W, heads, D)) for _ in range(3))
+
+    def pad(x, fill_extra):
+        g = np.zeros((B, T, Hp, Wp, heads, D + 1))
+        g[:, :, :H, :W, :, :D] = x.reshape(B, T, H, W, heads, D)
+        g[..., D] = fill_extra(np.pad(np.ones((H, W)), ((0, Hp - H), (0, Wp - W)))[None, None, :, :, None])
+        return g.reshape(B, T * Hp * Wp, heads, D + 1)
+
+    big = 1e9
+    qp = pad(q, lambda real: np.ones_like(real))          # extra channel of q is 1
+    kp = pad(k, lambda real: (real - 1.0) * big)          # extra channel of k is 0 for real keys, -1e9 for padding
+    vp = pad(v, lambda real: np.zeros_like(real))
+    full = oracle.skiparse_attention(qp, kp, vp, T, Hp, Wp, s, pattern, 0.4)[..., :D]
+    want = full.reshape(B, T, Hp, Wp, heads, D)[:, :, :H, :W].reshape(B, T * H * W, heads, D)
+    rows = _all_rows(B, heads, T * H * W)
+    got = oracle.skiparse_attention_rows_padded(q, k, v, rows, T, H, W, s, pattern, 0.4)
+    assert np.allclose(got, np.stack([want[b, n, h] for b, h, n in rows]), rtol=1e-9, atol=1e-11)
+    brute = oracle.masked_dense_attention(q, k, v, T, H, W, s, pattern, 0.4)
+    assert np.allclose(got, np.stack([brute[b, n, h] for b, h, n in rows]), rtol=1e-12, atol=1e-14)
