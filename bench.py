@@ -160,6 +160,12 @@ def main() -> int:
             extras["unpermute_ms"] = round(up_ms, 4)
             extras["unpermute_GBps"] = round(2 * tensor_bytes / up_ms / 1e6, 1)
             extras["permute_frac_of_hbm_peak"] = round(2 * tensor_bytes / p_ms / 1e6 / PEAK_HBM_GBS, 4)
+            if "group" in w.patterns:
+                yg = ws[tensor_bytes : 2 * tensor_bytes].view(torch.bfloat16).view(s * s * w.B, w.Nsub, w.heads, w.D)
+                sw_ms = time_calls(lambda: sk.skiparse_switch_pattern(yp, T, H, W, s, "token", out=yg), 10, 2)
+                extras["switch_tsa_to_gsa_ms"] = round(sw_ms, 4)
+                extras["switch_GBps"] = round(2 * tensor_bytes / sw_ms / 1e6, 1)
+                del yg
             del yp
         del ws
     if "dense" in sections:

@@ -56,6 +56,14 @@ int skiparse_unpermute(const void* src, void* dst, int B, int heads, int T, int 
                        int dtype, void* stream);
 
 /*
+ * Direct switch between the two sparse layouts (Alg. 1, tsa_to_gsa / gsa_to_tsa): src is in the sparse layout of
+ * `from_pattern`, dst receives the sparse layout of the other pattern; equal to unpermute(from) followed by permute(other)
+ * with a single row move per token.  Needs H and W multiples of s*s (both patterns must exist).  Bit-exact, any element type.
+ */
+int skiparse_switch_pattern(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s,
+                            int from_pattern, int dtype, void* stream);
+
+/*
  * Full attention (the dense blocks of the hybrid model, Sec. 3.4; also the per-subsequence step of Sec. 3.1):
  * for every (b, head):  out = softmax(q k^T * scale) v  over all N = T*H*W tokens, no mask, no dropout.
  * q, k, v, out: [B][N][heads][head_dim] bf16 (only N = T*H*W matters).  scale <= 0 selects 1/sqrt(head_dim).

@@ -50,6 +50,8 @@ def _load():
         lib.oracle_permute.argtypes = [vp, vp, i, i, i, i, i64, i, i]
         lib.oracle_unpermute.restype = i
         lib.oracle_unpermute.argtypes = [vp, vp, i, i, i, i, i64, i, i]
+        lib.oracle_switch_pattern.restype = i
+        lib.oracle_switch_pattern.argtypes = [vp, vp, i, i, i, i, i64, i, i]
         lib.oracle_attention.restype = i
         lib.oracle_attention.argtypes = [vp, vp, vp, vp, i64, i64, i, i, dbl, i]
         lib.oracle_skiparse_attention.restype = i
@@ -239,4 +241,15 @@ def skiparse_attention_rows_padded(q, k, v, rows, T: int, H: int, W: int, s: int
         ),
         "skiparse_attention_rows_padded",
     )
+    return out
+
+
+def switch_pattern(y: np.ndarray, T: int, H: int, W: int, s: int, from_pattern: str) -> np.ndarray:
+    """Sparse layout of `from_pattern` -> sparse layout of the other pattern (Alg. 1, tsa_to_gsa / gsa_to_tsa)."""
+    y = np.ascontiguousarray(y)
+    B = y.shape[0] // (s * s)
+    if y.shape[0] != B * s * s or y.shape[1] * s * s != T * H * W:
+        raise ValueError("sparse-layout shape does not match the grid")
+    out = np.empty_like(y)
+    _check(_load().oracle_switch_pattern(_ptr(y), _ptr(out), B, T, H, W, y.strides[1], s, PATTERNS[from_pattern]), "switch_pattern")
     return out

@@ -138,6 +138,25 @@ int oracle_unpermute(const void *y, void *x, int B, int T, int H, int W, int64_t
 }
 
 /*
+ * Direct switch between the two sparse layouts (Alg. 1, tsa_to_gsa / gsa_to_tsa): the same tokens, re-sorted from the
+ * subsequences of one pattern into those of the other.  Written as the composition it abbreviates: back to the original
+ * order with the inverse of `from_pattern`, then forward with the other pattern.  Both patterns must be valid for the grid
+ * (H and W multiples of s*s).
+ */
+int oracle_switch_pattern(const void *y_from, void *y_to, int B, int T, int H, int W, int64_t row_bytes, int s, int from_pattern)
+{
+    if (!y_from || !y_to || row_bytes < 1 || !shape_ok(B, T, H, W, s, ORACLE_GROUP)) return -1;
+    if (from_pattern != ORACLE_TOKEN && from_pattern != ORACLE_GROUP) return -1;
+    int to_pattern = from_pattern == ORACLE_TOKEN ? ORACLE_GROUP : ORACLE_TOKEN;
+    void *x = malloc((size_t)((int64_t)B * T * H * W * row_bytes));
+    if (!x) return -2;
+    int rc = oracle_unpermute(y_from, x, B, T, H, W, row_bytes, s, from_pattern);
+    if (rc == 0) rc = oracle_permute(x, y_to, B, T, H, W, row_bytes, s, to_pattern);
+    free(x);
+    return rc;
+}
+
+/*
  * One attention output row, plain definition:
  *   S[j] = scale * sum_d Q[d]*K[j][d];  m = max_j S[j];  P[j] = exp(S[j]-m);  O[:] = sum_j P[j] V[j][:] / sum_j P[j]
  * Key/value row j lives at element offset kv_off[j] (so that callers can walk a subsequence of a

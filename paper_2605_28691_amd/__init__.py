@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.skiparse_permute.argtypes = [vp, vp] + [i] * 9 + [vp]
         L.skiparse_unpermute.restype = i
         L.skiparse_unpermute.argtypes = [vp, vp] + [i] * 9 + [vp]
+        L.skiparse_switch_pattern.restype = i
+        L.skiparse_switch_pattern.argtypes = [vp, vp] + [i] * 9 + [vp]
         L.dense_attn_fwd.restype = i
         L.dense_attn_fwd.argtypes = [vp] * 4 + [i] * 6 + [f, i, vp]
         L.skiparse_attn_fwd.restype = i
@@ -109,6 +111,21 @@ def skiparse_unpermute(y: torch.Tensor, T: int, H: int, W: int, s: int, pattern:
     _check(
         lib().skiparse_unpermute(_dev(y, "y"), _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[pattern], _DTYPES[y.dtype], _stream()),
         "skiparse_unpermute",
+    )
+    return out
+
+
+def skiparse_switch_pattern(y: torch.Tensor, T: int, H: int, W: int, s: int, from_pattern: str, out: torch.Tensor | None = None):
+    """Sparse layout of `from_pattern` -> sparse layout of the other pattern, one row move per token."""
+    SB, Nsub, heads, D = y.shape
+    B = SB // (s * s)
+    if SB != B * s * s or Nsub * s * s != T * H * W:
+        raise ValueError("sparse-layout shape does not match the grid")
+    if out is None:
+        out = torch.empty_like(y)
+    _check(
+        lib().skiparse_switch_pattern(_dev(y, "y"), _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[from_pattern], _DTYPES[y.dtype], _stream()),
+        "skiparse_switch_pattern",
     )
     return out
 

@@ -161,6 +161,25 @@ int skiparse_unpermute(const void* src, void* dst, int B, int heads, int T, int 
     return permute_common(src, dst, B, heads, T, H, W, head_dim, s, pattern, dtype, stream, 0);
 }
 
+int skiparse_switch_pattern(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s,
+                            int from_pattern, int dtype, void* stream) {
+    if (!src || !dst) return SKIPARSE_EINVAL;
+    const int esz = elem_size(dtype);
+    if (esz == 0) return SKIPARSE_EINVAL;
+    if (from_pattern != SKIPARSE_TOKEN && from_pattern != SKIPARSE_GROUP) return SKIPARSE_EINVAL;
+    Shape sh;
+    const int rc = check_shape(B, heads, T, H, W, head_dim, s, SKIPARSE_GROUP, &sh);  // both patterns must fit: multiples of s*s
+    if (rc != SKIPARSE_OK) return rc;
+    if (misaligned(src) || misaligned(dst)) return SKIPARSE_EINVAL;
+    const size_t row_bytes = sh.row_elems * (size_t)esz;
+    if (row_bytes % 16 != 0) return SKIPARSE_EUNSUPPORTED;
+    if (overlap(src, dst, sh.elems * (size_t)esz)) return SKIPARSE_EINVAL;
+    if (s == 1) return finish(launch_permute(src, dst, B, make_gridmap(T, H, W, 1, SKIPARSE_TOKEN), row_bytes, 1, (hipStream_t)stream));
+    const int to_pattern = from_pattern == SKIPARSE_TOKEN ? SKIPARSE_GROUP : SKIPARSE_TOKEN;
+    const GridMap g_to = make_gridmap(T, H, W, s, to_pattern);
+    return finish(launch_switch(src, dst, B, g_to, from_pattern == SKIPARSE_GROUP, H, row_bytes, (hipStream_t)stream));
+}
+
 int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
                    int head_dim, float scale, int dtype, void* stream) {
     Shape sh;

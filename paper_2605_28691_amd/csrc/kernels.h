@@ -13,6 +13,10 @@ namespace skiparse {
 hipError_t launch_permute(const void* src, void* dst, int B, const GridMap& g, size_t row_bytes, int to_sparse,
                           hipStream_t stream);
 
+// Row moves from the sparse layout of one pattern to that of the other; g_to describes the destination pattern.
+hipError_t launch_switch(const void* src, void* dst, int B, const GridMap& g_to, int from_group, int H, size_t row_bytes,
+                         hipStream_t stream);
+
 // Flash-attention forward, bf16.  Units are (batch-like index, head); with g.mode == MODE_DENSE the batch-like
 // index is a batch element of n_sub tokens, otherwise it is a subsequence (p, q, b) addressed inside the
 // original layout through src_token().

@@ -31,7 +31,8 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
-            "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error"} <= set(names)
+            "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
+            "skiparse_switch_pattern"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -123,3 +124,11 @@ def test_attention_rejects_out_of_range_sizes(lib):
     assert lib.dense_attn_fwd(a[0], a[1], a[2], a[3], 1, 1, 1 << 8, 1 << 8, 1 << 8, 64, f, 0, None) == -2
     # one batch element of 4 GiB or more: beyond the 32-bit row offsets
     assert lib.dense_attn_fwd(a[0], a[1], a[2], a[3], 1, 64, 1 << 6, 1 << 6, 1 << 6, 128, f, 0, None) == -2
+
+
+def test_switch_pattern_rejects_bad_arguments(lib):
+    p, q = ctypes.c_void_p(FAKE), ctypes.c_void_p(FAKE + (1 << 30))
+    assert lib.skiparse_switch_pattern(None, q, 1, 2, 2, 8, 8, 64, 2, 0, 0, None) == -1
+    assert lib.skiparse_switch_pattern(p, p, 1, 2, 2, 8, 8, 64, 2, 0, 0, None) == -1
+    assert lib.skiparse_switch_pattern(p, q, 1, 2, 2, 8, 8, 64, 2, 3, 0, None) == -1  # unknown pattern
+    assert lib.skiparse_switch_pattern(p, q, 1, 2, 2, 6, 8, 64, 2, 0, 0, None) == -2  # token-wise alone would accept H = 6, the switch needs H % 4 == 0

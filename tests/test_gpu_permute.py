@@ -77,3 +77,37 @@ def test_permute_does_not_touch_neighbouring_memory():
     sk.skiparse_permute(x, T, H, W, s, "group", out=out)
     torch.cuda.synchronize()
     assert (buf[:2048] == 7.0).all() and (buf[2048 + n :] == 7.0).all()
+
+
+@pytest.mark.parametrize("B,heads,D,T,H,W,s,dtype", [
+    (1, 2, 64, 2, 8, 8, 2, torch.float32),
+    (2, 3, 128, 3, 8, 12, 2, torch.bfloat16),
+    (1, 5, 128, 2, 9, 18, 3, torch.bfloat16),
+    (3, 1, 64, 1, 16, 32, 4, torch.bfloat16),
+    (1, 7, 128, 2, 8, 8, 2, torch.uint8),
+    (2, 2, 64, 2, 3, 5, 1, torch.bfloat16),
+])
+@pytest.mark.parametrize("from_pattern", ["token", "group"])
+def test_switch_pattern_bit_exact(B, heads, D, T, H, W, s, dtype, from_pattern):
+    """skiparse_switch_pattern against the oracle's composition unpermute(from) -> permute(other), byte for byte."""
+    import paper_2605_28691_amd as sk
+
+    y = _random_bits((s * s * B, T * H * W // (s * s), heads, D), dtype, seed=7 * B + s)
+    yb = y.view(torch.uint8).reshape(y.shape[0], y.shape[1], -1).numpy()
+    want = oracle.switch_pattern(yb, T, H, W, s, from_pattern)
+    got = sk.skiparse_switch_pattern(y.cuda(), T, H, W, s, from_pattern)
+    assert np.array_equal(got.cpu().view(torch.uint8).reshape(want.shape).numpy(), want)
+
+
+def test_switch_pattern_768p_equals_two_step():
+    """At the 768P shape: the one-step switch equals unpermute + permute done by the library itself (both already checked
+    against the oracle), in both directions."""
+    import paper_2605_28691_amd as sk
+
+    w = si.WORKLOADS["768p"]
+    g = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.randint(-32768, 32767, (w.B, w.N, w.heads, w.D), generator=g, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    tsa = sk.skiparse_permute(x, w.T, w.H, w.W, w.s, "token")
+    gsa = sk.skiparse_permute(x, w.T, w.H, w.W, w.s, "group")
+    assert torch.equal(sk.skiparse_switch_pattern(tsa, w.T, w.H, w.W, w.s, "token").view(torch.int16), gsa.view(torch.int16))
+    assert torch.equal(sk.skiparse_switch_pattern(gsa, w.T, w.H, w.W, w.s, "group").view(torch.int16), tsa.view(torch.int16))

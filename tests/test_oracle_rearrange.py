@@ -183,3 +183,20 @@ def test_bad_shapes_rejected():
     with pytest.raises(ValueError):
         oracle.permute(np.zeros((1, 2 * 5 * 8, 1), dtype=np.float32), 2, 5, 8, 2, "token")
     oracle.permute(x, 2, 6, 8, 2, "token")  # multiples of s are enough for token-wise
+
+
+@pytest.mark.parametrize("B,T,H,W,s", [(1, 2, 8, 8, 2), (2, 3, 8, 12, 2), (1, 2, 9, 18, 3), (2, 1, 16, 32, 4)])
+def test_switch_pattern_matches_reshape_formulation(B, T, H, W, s):
+    """Alg. 1, tsa_to_gsa / gsa_to_tsa as axis moves: in the token-wise layout the class is (h%s, w%s) = (p2, q2) and the
+    position splits as (t, h_o, p1, w_o, q1); the group-wise layout has class (p1, q1) and position (t, h_o, p2, w_o, q2)."""
+    rng = np.random.default_rng(9)
+    N = T * H * W
+    x = rng.standard_normal((B, N, 3)).astype(np.float32)
+    tsa = oracle.permute(x, T, H, W, s, "token")
+    gsa = oracle.permute(x, T, H, W, s, "group")
+    u = s * s
+    a = tsa.reshape(s, s, B, T, H // u, s, W // u, s, 3)           # p2 q2 b t ho p1 wo q1 c
+    want_gsa = np.ascontiguousarray(a.transpose(5, 7, 2, 3, 4, 0, 6, 1, 8)).reshape(u * B, N // u, 3)  # p1 q1 b t ho p2 wo q2 c
+    assert np.array_equal(want_gsa, gsa)
+    assert np.array_equal(oracle.switch_pattern(tsa, T, H, W, s, "token"), gsa)
+    assert np.array_equal(oracle.switch_pattern(gsa, T, H, W, s, "group"), tsa)
