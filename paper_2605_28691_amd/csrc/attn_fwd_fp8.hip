@@ -8,7 +8,7 @@
 //     P8 = e4m3(P * sv / sv_max * 16)          the key block's V scale is folded into the probabilities
 //     O  = (P8 v8) * sv_max / 16 / sum(P)      fp32 accumulation, bf16 result
 // Both products use v_mfma_f32_32x32x64_f8f6f4 (64-deep contraction, twice the bf16 rate), transposed as in the bf16
-// kernel (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query.  A workgroup is 8 wavefronts x 32 queries; a
+// kernel (S^T = K Q^T, O^T = V^T P^T) so that each lane owns one query.  A workgroup is 4 wavefronts x 32 queries; a
 // wavefront's queries lie inside one 128-position scale block; keys are walked in tiles of 64, which never straddle one.
 //   * The probabilities leave the accumulators as 16 values per 32-key block in the accumulator's key order (4h..4h+3,
 //     8+4h..); packed to bytes, one v_permlane32_swap per 16 keys turns that into 8 consecutive keys per lane half,
@@ -29,7 +29,9 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
 constexpr int KT8 = 64;            // keys per tile = contraction depth of one PV MFMA
-constexpr int NW8 = 8;             // wavefronts per workgroup: 256 queries (two scale blocks) share each K/V tile
+constexpr int NW8 = 4;             // wavefronts per workgroup: 128 queries (one scale block) share each K/V tile
+constexpr int WAVES_PER_SIMD8 = 3; // three workgroups per compute unit: the kernel is not software-pipelined, the overlap of one
+                                   // wavefront's exponentials with another's MFMAs comes from occupancy (needs <= 168 VGPRs)
 constexpr int NT8 = 64 * NW8;
 constexpr float P_GAIN = 16.0f;    // probabilities are multiplied by (sv / sv_max) * 16 before the E4M3 cast
 
@@ -42,6 +44,7 @@ __device__ inline void lane_pair_f(float x, float& lo, float& hi) {
 }
 
 template <int D>
+__attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD8, WAVES_PER_SIMD8)))
 __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
     constexpr int NJ = D / 64;         // 64-channel MFMA steps of S^T = K Q^T
     constexpr int MT = D / 32;         // 32-channel blocks of O^T
@@ -49,7 +52,8 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     constexpr int V_STRIDE = D + 32;
     constexpr int K_BYTES = KT8 * K_STRIDE, V_BYTES = KT8 * V_STRIDE;
     constexpr int CH = D / 16;         // 16-byte chunks per row
-    constexpr int TPR = (NT8 / KT8 < CH) ? NT8 / KT8 : CH;  // threads that stage one row of a tile
+    constexpr int TPR_MAX = NT8 / KT8 >= 8 ? 8 : NT8 / KT8 >= 4 ? 4 : NT8 / KT8 >= 2 ? 2 : 1;
+    constexpr int TPR = TPR_MAX < CH ? TPR_MAX : CH;  // threads that stage one row of a tile (a power of two)
     constexpr int CPT = CH / TPR;      // 16-byte chunks per staging thread
     __shared__ __attribute__((aligned(16))) char lds[2 * K_BYTES + 2 * V_BYTES];
     __shared__ float sv_part[NW8];
@@ -136,13 +140,20 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     store_tile(0);
     __syncthreads();
 
+    float sk_cur = skp[0], sv_cur = svp[0], sk_nxt, sv_nxt;
     for (uint32_t t = 0; t < n_kt; t++) {
         const bool more = t + 1 < n_kt;
         if (more) load_tile(t + 1);
         const char* kb = lds_k + (t & 1u) * K_BYTES;
         const char* vb = lds_v + (t & 1u) * V_BYTES;
-        const float ct = cq * skp[t >> 1];            // logits -> log2 units for this key block
-        const float pg = svp[t >> 1] * p_gain;        // V scale of this key block, relative to the largest, times the gain
+        const float ct = cq * sk_cur;        // logits -> log2 units for this key block
+        const float pg = sv_cur * p_gain;    // V scale of this key block, relative to the largest, times the gain
+        {   // the next tile's scales are fetched a tile ahead so that no tile waits for them
+            uint32_t nb = (t + 1u) >> 1;
+            nb = nb < n_blk ? nb : n_blk - 1u;
+            sk_nxt = skp[nb];
+            sv_nxt = svp[nb];
+        }
 
         // S^T = K Q^T: two blocks of 32 keys
         f32x16 sacc[2];
@@ -237,6 +248,8 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
             oacc[mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pb, oacc[mt], 0, 0, 0, 0, 0, 0);
         }
         if (more) store_tile((t + 1) & 1u);
+        sk_cur = sk_nxt;
+        sv_cur = sv_nxt;
         __syncthreads();
     }
 
