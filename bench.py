@@ -54,8 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="768p", choices=["480p", "768p"])
     ap.add_argument("--cpu-rows", type=int, default=16384, help="query rows the oracle computes for cpu_baseline")
     ap.add_argument("--skip-extras", action="store_true", help="only the headline timing (used under the profiler)")
-    ap.add_argument("--extras", default="group,unfused,permute,dense,fp8,pad,cpu",
-                    help="comma list of the extra sections to run: group, unfused, permute, dense, fp8, pad (720P-shaped grid in the "
+    ap.add_argument("--extras", default="group,unfused,permute,chain,dense,fp8,pad,cpu",
+                    help="comma list of the extra sections to run: group, unfused, permute, chain (sparse layout in, other pattern's layout out), dense, fp8, pad (720P-shaped grid in the "
                          "any-resolution mode), cpu (oracle baseline + parity)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -168,6 +168,14 @@ def main() -> int:
                 del yg
             del yp
         del ws
+    if "chain" in sections and "group" in w.patterns:
+        # a block of a chain: q, k, v already in the token-wise sparse layout, output written in the group-wise layout
+        qs, ks, vs = (sk.skiparse_permute(t, T, H, W, s, "token") for t in (qd, kd, vd))
+        os_ = torch.empty_like(qs)
+        c_ms = time_calls(lambda: sk.skiparse_attn_fwd_sparse(qs, ks, vs, T, H, W, s, "token", "other", scale=w.scale, out=os_), it, 1)
+        extras["chain_token_to_group_ms"] = round(c_ms, 4)
+        extras["chain_token_to_group_tflops"] = round(flops / c_ms / 1e9, 2)
+        del qs, ks, vs, os_
     if "dense" in sections:
         d_ms = time_calls(lambda: sk.dense_attn_fwd(qd, kd, vd, T, H, W, scale=w.scale, out=out), 3, 1)
         extras["dense_ms"] = round(d_ms, 4)

@@ -33,6 +33,7 @@ extern "C" {
 enum { SKIPARSE_TOKEN = 0, SKIPARSE_GROUP = 1 };                       /* pattern */
 enum { SKIPARSE_BF16 = 0, SKIPARSE_FP32 = 1, SKIPARSE_FP8_E4M3 = 2 };  /* element type of a tensor */
 enum { SKIPARSE_FUSED = 1u, SKIPARSE_PAD = 2u };                       /* flags of skiparse_attn_fwd */
+enum { SKIPARSE_OUT_SAME = 0, SKIPARSE_OUT_OTHER = 1, SKIPARSE_OUT_ORIGINAL = 2 }; /* out_layout of skiparse_attn_fwd_sparse */
 
 enum {
     SKIPARSE_OK = 0,
@@ -93,6 +94,19 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
 
 /* Bytes of device workspace skiparse_attn_fwd needs for these arguments (0 for the fused path, 0 on bad arguments). */
 size_t skiparse_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int dtype, unsigned flags);
+
+/*
+ * Attention for a chain of sparse blocks (Sec. 3.1: token-wise and group-wise blocks alternate; Alg. 1, tsa_to_gsa /
+ * gsa_to_tsa): q, k, v are ALREADY in the sparse layout of `pattern` ([s*s*B][T*H*W/(s*s)][heads][head_dim] bf16), so every
+ * subsequence is contiguous and no gather is needed; the result row of each query is written straight to
+ *   SKIPARSE_OUT_SAME      the same sparse layout,
+ *   SKIPARSE_OUT_OTHER     the sparse layout of the other pattern (what the next block reads; needs H, W multiples of s*s),
+ *   SKIPARSE_OUT_ORIGINAL  the original layout (after the last sparse block).
+ * Equal to dense attention over the s*s*B subsequences followed by skiparse_switch_pattern / skiparse_unpermute, without the
+ * extra pass over the tensor.  out must not overlap q, k or v.  Other rules as for skiparse_attn_fwd.
+ */
+int skiparse_attn_fwd_sparse(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
+                             int head_dim, int s, int pattern, int out_layout, float scale, int dtype, void* stream);
 
 /*
  * 8-bit variant (motivated by Sec. 3.5, which runs the attention MatMuls in an 8-bit format; here OCP fp8 e4m3

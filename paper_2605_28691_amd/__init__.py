@@ -19,6 +19,7 @@ BF16, FP32, FP8_E4M3 = 0, 1, 2
 FUSED = 1
 PAD = 2
 PATTERNS = {"token": TOKEN, "group": GROUP}
+OUT_LAYOUTS = {"same": 0, "other": 1, "original": 2}
 _DTYPES = {torch.bfloat16: BF16, torch.float32: FP32, torch.uint8: FP8_E4M3, torch.float8_e4m3fn: FP8_E4M3}
 
 _lib = None
@@ -52,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.dense_attn_fwd.argtypes = [vp] * 4 + [i] * 6 + [f, i, vp]
         L.skiparse_attn_fwd.restype = i
         L.skiparse_attn_fwd.argtypes = [vp] * 4 + [i] * 8 + [f, i, u, vp, sz, vp]
+        L.skiparse_attn_fwd_sparse.restype = i
+        L.skiparse_attn_fwd_sparse.argtypes = [vp] * 4 + [i] * 9 + [f, i, vp]
         L.skiparse_workspace_bytes.restype = sz
         L.skiparse_workspace_bytes.argtypes = [i] * 8 + [u]
         L.skiparse_quantize_fp8.restype = i
@@ -166,6 +169,25 @@ def skiparse_attn_fwd(q, k, v, T: int, H: int, W: int, s: int, pattern: str, sca
                                 PATTERNS[pattern], float(scale), _DTYPES[q.dtype], (FUSED if fused else 0) | (PAD if pad else 0), ws_ptr, ws_bytes,
                                 _stream()),
         "skiparse_attn_fwd",
+    )
+    return out
+
+
+def skiparse_attn_fwd_sparse(q, k, v, T: int, H: int, W: int, s: int, pattern: str, out_layout: str = "other", scale: float = 0.0,
+                             out: torch.Tensor | None = None):
+    """Attention on tensors already in the sparse layout of `pattern` ([s*s*B][N/s^2][heads][D]); the output goes to the
+    same layout ("same"), the other pattern's sparse layout ("other") or the original layout ("original")."""
+    SB, Nsub, heads, D = q.shape
+    B = SB // (s * s)
+    if SB != B * s * s or Nsub * s * s != T * H * W:
+        raise ValueError("sparse-layout shape does not match the grid")
+    if out is None:
+        shape = (B, T * H * W, heads, D) if out_layout == "original" else tuple(q.shape)
+        out = torch.empty(shape, dtype=q.dtype, device=q.device)
+    _check(
+        lib().skiparse_attn_fwd_sparse(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), B, heads, T, H, W, D, s,
+                                       PATTERNS[pattern], OUT_LAYOUTS[out_layout], float(scale), _DTYPES[q.dtype], _stream()),
+        "skiparse_attn_fwd_sparse",
     )
     return out
 

@@ -197,6 +197,7 @@ int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B
     a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
     a.g = make_dense_gridmap(sh.n_tok);
     a.pad = false;
+    a.out_kind = OUT_AS_INPUT;
     return finish(launch_attn_bf16(a, (hipStream_t)stream));
 }
 
@@ -226,6 +227,7 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
     AttnArgs a;
     a.B = B; a.heads = heads; a.head_dim = head_dim;
     a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+    a.out_kind = OUT_AS_INPUT;
     hipStream_t st = (hipStream_t)stream;
     if (flags & SKIPARSE_FUSED) {
         a.q = q; a.k = k; a.v = v; a.out = out;
@@ -255,6 +257,35 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
     a.pad = false;
     if ((e = launch_attn_bf16(a, st)) != hipSuccess) return finish(e);
     return finish(launch_permute(op, out, B, g, row_bytes, 0, st));
+}
+
+int skiparse_attn_fwd_sparse(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int H, int W,
+                             int head_dim, int s, int pattern, int out_layout, float scale, int dtype, void* stream) {
+    if (out_layout != SKIPARSE_OUT_SAME && out_layout != SKIPARSE_OUT_OTHER && out_layout != SKIPARSE_OUT_ORIGINAL)
+        return SKIPARSE_EINVAL;
+    Shape sh;
+    // the other pattern's layout exists only when both patterns do: multiples of s*s
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, out_layout == SKIPARSE_OUT_OTHER ? SKIPARSE_GROUP : pattern, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (pattern != SKIPARSE_TOKEN && pattern != SKIPARSE_GROUP) return SKIPARSE_EINVAL;
+    if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
+    if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
+    rc = check_attn_ranges(sh, W, 2);
+    if (rc != SKIPARSE_OK) return rc;
+    rc = check_attn_ptrs(q, k, v, out, sh.elems * 2);
+    if (rc != SKIPARSE_OK) return rc;
+    AttnArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = out;
+    a.B = B * s * s;  // the subsequences are the batch of the attention (Alg. 1: "(p q b)")
+    a.heads = heads; a.head_dim = head_dim;
+    a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+    a.g = make_dense_gridmap(sh.n_sub);
+    a.pad = false;
+    // with s = 1 every layout is the original one
+    a.out_kind = (out_layout == SKIPARSE_OUT_SAME || s == 1) ? OUT_AS_INPUT : out_layout == SKIPARSE_OUT_ORIGINAL ? OUT_ORIGINAL : OUT_OTHER_PATTERN;
+    a.out_B = B;
+    a.g_in = make_gridmap(T, H, W, s, pattern);
+    return finish(launch_attn_bf16(a, (hipStream_t)stream));
 }
 
 int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,

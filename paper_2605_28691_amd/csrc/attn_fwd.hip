@@ -97,6 +97,30 @@ __device__ inline size_t uniform(size_t x) {
 // GROUP selects the group-wise index map (two extra divisions by s per staged row); token-wise and dense use GROUP = false.
 // PAD selects the any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s, padding positions
 // are masked as keys (a validity byte per staged row in LDS) and skipped as queries; every block takes the masked step.
+// Row of `out` for position j of subsequence sb of the input's sparse layout: the token's row in the original layout, or its
+// row in the sparse layout of the other pattern (Alg. 1: tsa_to_orig / gsa_to_orig, tsa_to_gsa / gsa_to_tsa).
+__device__ inline size_t scattered_row(const AttnArgs& a, uint32_t sb, uint32_t j) {
+    const GridMap& gi = a.g_in;
+    const uint32_t s = (uint32_t)gi.s, W = (uint32_t)gi.W, B = (uint32_t)a.out_B;
+    const uint32_t pq = sb / B, b = sb - pq * B;
+    const uint32_t n = src_token(gi, pq / s, pq % s, j);
+    if (a.out_kind == OUT_ORIGINAL) return (size_t)b * (uint32_t)gi.n_tok + n;
+    const uint32_t th = n / W, w = n - th * W;  // th = t*H + h
+    uint32_t p, q, r, ws;
+    if (gi.b != 0) {  // input group-wise -> output token-wise
+        p = th % s;
+        q = w % s;
+        r = th / s;
+        ws = w / s;
+    } else {          // input token-wise -> output group-wise
+        p = (th / s) % s;
+        q = (w / s) % s;
+        r = (th / (s * s)) * s + th % s;
+        ws = (w / (s * s)) * s + w % s;
+    }
+    return ((size_t)(p * s + q) * B + b) * (uint32_t)gi.n_sub + r * (W / s) + ws;
+}
+
 template <int D, int QT, bool GROUP, bool PAD>
 __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
     using TL = Tile<D>;
@@ -525,6 +549,12 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         lane_pair(l_run[qi], llo, lhi);
         const float inv = 1.0f / (llo + lhi);
         if (q_valid[qi]) {
+            __bf16* orow = Og + q_row_off[qi];
+            if (a.out_kind != OUT_AS_INPUT) {
+                // the input is a sparse layout: bb is the subsequence (p, q, b) and this lane's query sits at position jq of it
+                const uint32_t jq = qt * BR + (wave * QT + qi) * 32u + lq;
+                orow = (__bf16*)a.out + scattered_row(a, bb, jq) * C + (size_t)head * D;
+            }
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
 #pragma unroll
@@ -532,7 +562,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
                     bf16x4 o;
 #pragma unroll
                     for (int e = 0; e < 4; e++) o[e] = (__bf16)(oacc[qi][mt][g * 4 + e] * inv);
-                    *(bf16x4*)(Og + q_row_off[qi] + mt * 32 + g * 8 + 4 * h) = o;
+                    *(bf16x4*)(orow + mt * 32 + g * 8 + 4 * h) = o;
                 }
         }
     }

@@ -31,7 +31,14 @@ struct AttnArgs {
     float scale;    // multiplies the logits
     bool pad;       // any-resolution mode: g describes the padded grid, padding positions are masked / skipped
     GridMap g;
+    // Where the output rows go.  OUT_AS_INPUT: out is addressed like q.  OUT_ORIGINAL / OUT_OTHER_PATTERN: q, k, v are the
+    // sparse layout of pattern g_in (so g is a dense map over its B*s*s subsequences) and the row of query (sb, j) is written
+    // at its place in the original layout / in the sparse layout of the other pattern (Alg. 1, tsa_to_gsa / gsa_to_tsa).
+    int out_kind;
+    int out_B;      // batch elements of the original layout (only for out_kind != OUT_AS_INPUT)
+    GridMap g_in;   // index map of the input's pattern (only for out_kind != OUT_AS_INPUT)
 };
+enum OutKind : int { OUT_AS_INPUT = 0, OUT_ORIGINAL = 1, OUT_OTHER_PATTERN = 2 };
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
 
 // bf16 (original layout) -> E4M3 codes (sparse layout) + one float32 scale per (subsequence, head, 128 positions).

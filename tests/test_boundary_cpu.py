@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
-            "skiparse_switch_pattern"} <= set(names)
+            "skiparse_switch_pattern", "skiparse_attn_fwd_sparse"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -132,3 +132,19 @@ def test_switch_pattern_rejects_bad_arguments(lib):
     assert lib.skiparse_switch_pattern(p, p, 1, 2, 2, 8, 8, 64, 2, 0, 0, None) == -1
     assert lib.skiparse_switch_pattern(p, q, 1, 2, 2, 8, 8, 64, 2, 3, 0, None) == -1  # unknown pattern
     assert lib.skiparse_switch_pattern(p, q, 1, 2, 2, 6, 8, 64, 2, 0, 0, None) == -2  # token-wise alone would accept H = 6, the switch needs H % 4 == 0
+
+
+def test_attn_fwd_sparse_rejects_bad_arguments(lib):
+    a = [ctypes.c_void_p(FAKE + i * (1 << 30)) for i in range(4)]
+    f = ctypes.c_float(0.0)
+
+    def call(H, W, s, pattern, layout, out=a[3], D=64, dtype=0):
+        return lib.skiparse_attn_fwd_sparse(a[0], a[1], a[2], out, 1, 1, 1, H, W, D, s, pattern, layout, f, dtype, None)
+
+    assert call(12, 12, 2, 0, 3) == -1          # unknown output layout
+    assert call(12, 12, 2, 2, 0) == -1          # unknown pattern
+    assert call(6, 24, 2, 0, 1) == -2           # the other pattern's layout needs H, W multiples of s*s
+    assert call(12, 12, 2, 1, 0, out=a[0]) == -1  # out overlaps q
+    assert call(12, 12, 2, 0, 0, out=None) == -1
+    assert call(12, 12, 2, 0, 0, D=96) == -3    # no kernel for this head_dim
+    assert call(12, 12, 2, 0, 0, dtype=1) == -3  # bf16 only

@@ -1,0 +1,77 @@
+"""GPU parity: skiparse_attn_fwd_sparse (inputs already in a sparse layout, output written straight to the same layout, the
+other pattern's layout or the original layout) through the C ABI against the float64 oracle.
+
+The expected value is the oracle's Skiparse attention (original layout) moved, with the oracle's own permute, to the layout
+the call writes.  Tolerance (bf16 path): max |diff| <= 2e-2 and relative L2 error <= 5e-3.  Row placement is also checked
+bit for bit against the library's separate rearrangement calls (same arithmetic, only the destination row differs).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from _util import assert_close_bf16, oracle_inputs, to_np64
+
+pytestmark = pytest.mark.gpu
+
+CASES = [  # B, heads, D, T, H, W, s: H and W multiples of s*s so that both patterns exist
+    (1, 2, 64, 2, 8, 8, 2),      # 32 tokens per subsequence
+    (2, 3, 128, 3, 8, 12, 2),    # Nsub = 72, batch of 2
+    (1, 2, 128, 5, 16, 20, 2),   # Nsub = 400: several query and key tiles with tails
+    (1, 9, 128, 4, 9, 18, 3),    # s = 3, unit count not a multiple of 8
+    (1, 1, 64, 1, 16, 48, 4),    # s = 4
+]
+OTHER = {"token": "group", "group": "token"}
+
+
+def _sparse_gpu(sk, ts, T, H, W, s, pattern):
+    return tuple(sk.skiparse_permute(t.cuda(), T, H, W, s, pattern) for t in ts)
+
+
+@pytest.mark.parametrize("B,heads,D,T,H,W,s", CASES)
+@pytest.mark.parametrize("pattern", ["token", "group"])
+def test_sparse_input_all_output_layouts(B, heads, D, T, H, W, s, pattern):
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("chain", B, heads, D, T, H, W, s, seed=31 + s)
+    q, k, v = si.make_qkv(w)
+    want = oracle.skiparse_attention(*oracle_inputs(q, k, v), T, H, W, s, pattern, w.scale)  # original layout
+    qs, ks, vs = _sparse_gpu(sk, (q, k, v), T, H, W, s, pattern)
+    same = sk.skiparse_attn_fwd_sparse(qs, ks, vs, T, H, W, s, pattern, "same", scale=w.scale)
+    other = sk.skiparse_attn_fwd_sparse(qs, ks, vs, T, H, W, s, pattern, "other", scale=w.scale)
+    orig = sk.skiparse_attn_fwd_sparse(qs, ks, vs, T, H, W, s, pattern, "original", scale=w.scale)
+    assert_close_bf16(to_np64(orig), want, f"{pattern} -> original")
+    assert_close_bf16(to_np64(same), oracle.permute(want, T, H, W, s, pattern), f"{pattern} -> same")
+    assert_close_bf16(to_np64(other), oracle.permute(want, T, H, W, s, OTHER[pattern]), f"{pattern} -> other")
+    # placement, bit for bit: the three calls differ only in where a row is written
+    assert torch.equal(sk.skiparse_unpermute(same, T, H, W, s, pattern), orig)
+    assert torch.equal(sk.skiparse_switch_pattern(same, T, H, W, s, pattern), other)
+
+
+def test_sparse_input_s1_is_dense():
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("chain1", 1, 2, 128, 1, 10, 13, 1, seed=5)
+    q, k, v = si.make_qkv(w)
+    qg, kg, vg = (t.cuda() for t in (q, k, v))
+    want = sk.dense_attn_fwd(qg, kg, vg, 1, 10, 13, scale=w.scale)
+    for layout in ("same", "other", "original"):
+        assert torch.equal(sk.skiparse_attn_fwd_sparse(qg, kg, vg, 1, 10, 13, 1, "token", layout, scale=w.scale), want)
+
+
+def test_768p_token_to_group_sampled_rows():
+    """Full benchmark shape: token-wise block whose output lands in the group-wise layout; sampled rows against the oracle."""
+    import paper_2605_28691_amd as sk
+
+    w = si.WORKLOADS["768p"]
+    q, k, v = si.make_qkv(w)
+    qs, ks, vs = _sparse_gpu(sk, (q, k, v), w.T, w.H, w.W, w.s, "token")
+    out = sk.skiparse_attn_fwd_sparse(qs, ks, vs, w.T, w.H, w.W, w.s, "token", "other", scale=w.scale)
+    rows = si.sample_rows(w, 4, seed=3)  # (b, head, n) in the original layout
+    want = oracle.skiparse_attention_rows(*oracle_inputs(q, k, v), rows, w.T, w.H, w.W, w.s, "token", w.scale)
+    got = np.empty_like(want)
+    for i, (b, head, n) in enumerate(rows):
+        p, qq, j = oracle.dst_index("group", w.s, w.T, w.H, w.W, int(n))
+        got[i] = to_np64(out[(p * w.s + qq) * w.B + int(b), j, int(head)])
+    assert_close_bf16(got, want, "768p token -> group")
