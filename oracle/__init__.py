@@ -50,6 +50,12 @@ def _load():
         lib.oracle_permute.argtypes = [vp, vp, i, i, i, i, i64, i, i]
         lib.oracle_unpermute.restype = i
         lib.oracle_unpermute.argtypes = [vp, vp, i, i, i, i, i64, i, i]
+        lib.oracle_attention_bwd.restype = i
+        lib.oracle_attention_bwd.argtypes = [vp] * 7 + [i64, i64, i, i, dbl, i]
+        lib.oracle_skiparse_attention_bwd.restype = i
+        lib.oracle_skiparse_attention_bwd.argtypes = [vp] * 7 + [i] * 8 + [dbl, i]
+        lib.oracle_skiparse_attention_bwd_unit.restype = i
+        lib.oracle_skiparse_attention_bwd_unit.argtypes = [vp] * 5 + [i64] + [vp] * 3 + [i, i, i64] + [i] * 8 + [dbl, i]
         lib.oracle_switch_pattern.restype = i
         lib.oracle_switch_pattern.argtypes = [vp, vp, i, i, i, i, i64, i, i]
         lib.oracle_attention.restype = i
@@ -176,6 +182,53 @@ def skiparse_attention_rows(q, k, v, rows, T: int, H: int, W: int, s: int, patte
         "skiparse_attention_rows",
     )
     return out
+
+
+def attention_bwd(q, k, v, dout, scale: float):
+    """Gradients (dq, dk, dv) of :func:`attention` for dL/dout = dout; all [nb][n][heads][D], float64 results."""
+    code = _dtype_code(q, k, v, dout)
+    nb, n, heads, D = q.shape
+    dq, dk, dv = (np.empty(q.shape, dtype=np.float64) for _ in range(3))
+    _check(
+        _load().oracle_attention_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), nb, n, heads, D, float(scale), code),
+        "attention_bwd",
+    )
+    return dq, dk, dv
+
+
+def skiparse_attention_bwd(q, k, v, dout, T: int, H: int, W: int, s: int, pattern: str, scale: float):
+    """Gradients (dq, dk, dv) of :func:`skiparse_attention`, original layout in and out."""
+    code = _dtype_code(q, k, v, dout)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    dq, dk, dv = (np.empty(q.shape, dtype=np.float64) for _ in range(3))
+    _check(
+        _load().oracle_skiparse_attention_bwd(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), code
+        ),
+        "skiparse_attention_bwd",
+    )
+    return dq, dk, dv
+
+
+def skiparse_attention_bwd_unit(q, k, v, dout, b: int, head: int, toks, T: int, H: int, W: int, s: int, pattern: str, scale: float):
+    """Gradient rows (dq, dk, dv), each [len(toks)][D], for tokens `toks` of ONE attention unit: batch element b, head `head`
+    and the subsequence that holds toks[0] (every token listed must lie in it).  Walks the whole unit."""
+    code = _dtype_code(q, k, v, dout)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    toks = np.ascontiguousarray(np.asarray(toks, dtype=np.int64).reshape(-1))
+    dq, dk, dv = (np.empty((toks.shape[0], D), dtype=np.float64) for _ in range(3))
+    _check(
+        _load().oracle_skiparse_attention_bwd_unit(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(toks), toks.shape[0], _ptr(dq), _ptr(dk), _ptr(dv), int(b), int(head),
+            int(toks[0]), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), code,
+        ),
+        "skiparse_attention_bwd_unit",
+    )
+    return dq, dk, dv
 
 
 def masked_dense_attention(q, k, v, T: int, H: int, W: int, s: int, pattern: str, scale: float) -> np.ndarray:

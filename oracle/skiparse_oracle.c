@@ -432,6 +432,226 @@ double oracle_e4m3_decode(uint8_t code)
 uint8_t oracle_e4m3_encode(float y) { return e4m3_encode(y); }
 
 /*
+ * ---- Gradients (Sec. 4.1: the model is fine-tuned with the sparse attention in place, so the layer needs a backward pass).
+ *
+ * The forward definition O = softmax(scale Q K^T) V differentiated by hand, for a scalar loss with dL/dO = dO given:
+ *     P  = softmax(S),  S = scale Q K^T
+ *     dV = P^T dO
+ *     dP = dO V^T
+ *     dS = P o (dP - delta 1^T),   delta_i = sum_j P_ij dP_ij         (Jacobian of a row softmax)
+ *     dQ = scale dS K,   dK = scale dS^T Q
+ * Row i of dQ depends only on query i; rows of dK and dV sum over all queries.  Everything is float64, the N x N
+ * matrices are walked row by row and never stored.
+ */
+
+/* Softmax row of query i (probabilities into p[0..n_keys)) -- same two-pass form as attention_row. */
+static void softmax_row(const void *q, int64_t q_off, const void *k, const int64_t *kv_off, int64_t n_keys, int D, double scale,
+                        int dtype, double *p)
+{
+    double m = -INFINITY, denom = 0.0;
+    for (int64_t j = 0; j < n_keys; j++) {
+        double acc = 0.0;
+        for (int d = 0; d < D; d++) acc += load_elem(q, dtype, q_off + d) * load_elem(k, dtype, kv_off[j] + d);
+        p[j] = scale * acc;
+        if (p[j] > m) m = p[j];
+    }
+    for (int64_t j = 0; j < n_keys; j++) {
+        p[j] = exp(p[j] - m);
+        denom += p[j];
+    }
+    for (int64_t j = 0; j < n_keys; j++) p[j] /= denom;
+}
+
+/*
+ * Contribution of query row i to the gradients.  p = its softmax row (input), ds = scratch of n_keys doubles.
+ * dq_row (D doubles) is overwritten; dk / dv (may be NULL) are accumulated at dk[acc_off[j] + d] for every key j with
+ * acc_off[j] >= 0 (a negative offset means "this key's gradient is not wanted").
+ */
+static void bwd_row(const void *q, int64_t q_off, const void *k, const void *v, const void *dout, const int64_t *kv_off,
+                    int64_t n_keys, int D, double scale, int dtype, const double *p, double *ds, double *dq_row, double *dk,
+                    double *dv, const int64_t *acc_off)
+{
+    double delta = 0.0;
+    for (int64_t j = 0; j < n_keys; j++) {
+        double dp = 0.0;
+        for (int d = 0; d < D; d++) dp += load_elem(dout, dtype, q_off + d) * load_elem(v, dtype, kv_off[j] + d);
+        ds[j] = dp;
+        delta += p[j] * dp;
+    }
+    for (int64_t j = 0; j < n_keys; j++) ds[j] = p[j] * (ds[j] - delta);
+    if (dq_row) {
+        for (int d = 0; d < D; d++) dq_row[d] = 0.0;
+        for (int64_t j = 0; j < n_keys; j++)
+            for (int d = 0; d < D; d++) dq_row[d] += scale * ds[j] * load_elem(k, dtype, kv_off[j] + d);
+    }
+    if (dk && dv) {
+        for (int64_t j = 0; j < n_keys; j++) {
+            if (acc_off[j] < 0) continue;
+            for (int d = 0; d < D; d++) {
+                dk[acc_off[j] + d] += scale * ds[j] * load_elem(q, dtype, q_off + d);
+                dv[acc_off[j] + d] += p[j] * load_elem(dout, dtype, q_off + d);
+            }
+        }
+    }
+}
+
+/*
+ * Gradients of oracle_attention: q, k, v, dout are [nb][n][heads][D]; dq, dk, dv float64 of the same shape.
+ * One thread per (batch, head), so the accumulation into dk / dv needs no synchronisation.
+ */
+int oracle_attention_bwd(const void *q, const void *k, const void *v, const void *dout, double *dq, double *dk, double *dv,
+                         int64_t nb, int64_t n, int heads, int D, double scale, int dtype)
+{
+    if (!q || !k || !v || !dout || !dq || !dk || !dv || nb < 1 || n < 1 || heads < 1 || D < 1) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t C = (int64_t)heads * D;
+    int fail = 0;
+    memset(dk, 0, sizeof(double) * (size_t)(nb * n * C));
+    memset(dv, 0, sizeof(double) * (size_t)(nb * n * C));
+#pragma omp parallel
+    {
+        double *p = (double *)malloc(sizeof(double) * (size_t)n);
+        double *ds = (double *)malloc(sizeof(double) * (size_t)n);
+        int64_t *off = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+        if (!p || !ds || !off) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 1)
+            for (int64_t b = 0; b < nb; b++)
+                for (int hd = 0; hd < heads; hd++) {
+                    for (int64_t j = 0; j < n; j++) off[j] = (b * n + j) * C + (int64_t)hd * D;
+                    for (int64_t i = 0; i < n; i++) {
+                        softmax_row(q, off[i], k, off, n, D, scale, dtype, p);
+                        bwd_row(q, off[i], k, v, dout, off, n, D, scale, dtype, p, ds, dq + off[i], dk, dv, off);
+                    }
+                }
+        }
+        free(p);
+        free(ds);
+        free(off);
+    }
+    return fail ? -2 : 0;
+}
+
+/*
+ * Gradients of oracle_skiparse_attention, everything in the ORIGINAL layout: the rearrangement is a permutation of rows,
+ * so its transpose is the inverse rearrangement:
+ *     (dq, dk, dv) = unpermute( attention_bwd( permute(q), permute(k), permute(v), permute(dout) ) )      (Alg. 1)
+ */
+int oracle_skiparse_attention_bwd(const void *q, const void *k, const void *v, const void *dout, double *dq, double *dk,
+                                  double *dv, int B, int heads, int T, int H, int W, int D, int s, int pattern, double scale,
+                                  int dtype)
+{
+    if (!q || !k || !v || !dout || !dq || !dk || !dv || heads < 1 || D < 1 || !shape_ok(B, T, H, W, s, pattern)) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t esz = dtype == ORACLE_BF16 ? 2 : dtype == ORACLE_F32 ? 4 : 8;
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W, Nsub = N / (s * s);
+    size_t in_bytes = (size_t)(B * N * C * esz), g_bytes = (size_t)(B * N * C) * sizeof(double);
+    void *qp = malloc(in_bytes), *kp = malloc(in_bytes), *vp = malloc(in_bytes), *dop = malloc(in_bytes);
+    double *gq = (double *)malloc(g_bytes), *gk = (double *)malloc(g_bytes), *gv = (double *)malloc(g_bytes);
+    int rc = -2;
+    if (qp && kp && vp && dop && gq && gk && gv) {
+        oracle_permute(q, qp, B, T, H, W, C * esz, s, pattern);
+        oracle_permute(k, kp, B, T, H, W, C * esz, s, pattern);
+        oracle_permute(v, vp, B, T, H, W, C * esz, s, pattern);
+        oracle_permute(dout, dop, B, T, H, W, C * esz, s, pattern);
+        rc = oracle_attention_bwd(qp, kp, vp, dop, gq, gk, gv, (int64_t)B * s * s, Nsub, heads, D, scale, dtype);
+        int64_t grow = C * (int64_t)sizeof(double);
+        if (rc == 0) rc = oracle_unpermute(gq, dq, B, T, H, W, grow, s, pattern);
+        if (rc == 0) rc = oracle_unpermute(gk, dk, B, T, H, W, grow, s, pattern);
+        if (rc == 0) rc = oracle_unpermute(gv, dv, B, T, H, W, grow, s, pattern);
+    }
+    free(qp);
+    free(kp);
+    free(vp);
+    free(dop);
+    free(gq);
+    free(gk);
+    free(gv);
+    return rc;
+}
+
+/*
+ * Sampled mode for shapes whose full gradient is out of reach on a CPU: one attention unit -- batch element b, head hd and
+ * the subsequence that contains token n_any -- is walked completely (every query row of the unit), and the gradients are
+ * kept for a list of tokens of that unit only.  toks = [n_toks] token numbers n (all must lie in that subsequence);
+ * dq, dk, dv = [n_toks][D].  The query loop is split over threads with one private dk / dv accumulator each.
+ */
+int oracle_skiparse_attention_bwd_unit(const void *q, const void *k, const void *v, const void *dout, const int64_t *toks,
+                                       int64_t n_toks, double *dq, double *dk, double *dv, int b, int hd, int64_t n_any, int B,
+                                       int heads, int T, int H, int W, int D, int s, int pattern, double scale, int dtype)
+{
+    if (!q || !k || !v || !dout || !toks || !dq || !dk || !dv || n_toks < 1 || heads < 1 || D < 1 ||
+        !shape_ok(B, T, H, W, s, pattern))
+        return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W, Nsub = N / (s * s);
+    if (b < 0 || b >= B || hd < 0 || hd >= heads || n_any < 0 || n_any >= N) return -1;
+    int p0, q0;
+    int64_t j0;
+    oracle_dst_index(pattern, s, T, H, W, n_any, &p0, &q0, &j0);
+    int64_t *off = (int64_t *)malloc(sizeof(int64_t) * (size_t)Nsub);     /* element offset of key j */
+    int64_t *acc_off = (int64_t *)malloc(sizeof(int64_t) * (size_t)Nsub); /* where key j's gradient goes, or -1 */
+    int64_t *tok_j = (int64_t *)malloc(sizeof(int64_t) * (size_t)n_toks);
+    int rc = 0;
+    if (!off || !acc_off || !tok_j) rc = -2;
+    if (rc == 0) {
+        for (int64_t j = 0; j < Nsub; j++) {
+            off[j] = ((int64_t)b * N + oracle_src_index(pattern, s, T, H, W, p0, q0, j)) * C + (int64_t)hd * D;
+            acc_off[j] = -1;
+        }
+        for (int64_t t = 0; t < n_toks && rc == 0; t++) {
+            int pt, qt;
+            if (toks[t] < 0 || toks[t] >= N) { rc = -1; break; }
+            oracle_dst_index(pattern, s, T, H, W, toks[t], &pt, &qt, &tok_j[t]);
+            if (pt != p0 || qt != q0 || acc_off[tok_j[t]] >= 0) rc = -1; /* wrong subsequence, or listed twice */
+            else acc_off[tok_j[t]] = t * D;
+        }
+    }
+    if (rc == 0) {
+        int fail = 0;
+        memset(dk, 0, sizeof(double) * (size_t)(n_toks * D));
+        memset(dv, 0, sizeof(double) * (size_t)(n_toks * D));
+#pragma omp parallel
+        {
+            double *p = (double *)malloc(sizeof(double) * (size_t)Nsub);
+            double *ds = (double *)malloc(sizeof(double) * (size_t)Nsub);
+            double *dq_row = (double *)malloc(sizeof(double) * (size_t)D);
+            double *dk_loc = (double *)calloc((size_t)(n_toks * D), sizeof(double));
+            double *dv_loc = (double *)calloc((size_t)(n_toks * D), sizeof(double));
+            if (!p || !ds || !dq_row || !dk_loc || !dv_loc) {
+#pragma omp atomic write
+                fail = 1;
+            } else {
+#pragma omp for schedule(static)
+                for (int64_t i = 0; i < Nsub; i++) {
+                    softmax_row(q, off[i], k, off, Nsub, D, scale, dtype, p);
+                    bwd_row(q, off[i], k, v, dout, off, Nsub, D, scale, dtype, p, ds, dq_row, dk_loc, dv_loc, acc_off);
+                    if (acc_off[i] >= 0)
+                        for (int d = 0; d < D; d++) dq[acc_off[i] + d] = dq_row[d];
+                }
+#pragma omp critical
+                for (int64_t e = 0; e < n_toks * D; e++) {
+                    dk[e] += dk_loc[e];
+                    dv[e] += dv_loc[e];
+                }
+            }
+            free(p);
+            free(ds);
+            free(dq_row);
+            free(dk_loc);
+            free(dv_loc);
+        }
+        if (fail) rc = -2;
+    }
+    free(off);
+    free(acc_off);
+    free(tok_j);
+    return rc;
+}
+
+/*
  * Quantise x (bf16 bit patterns, ORIGINAL layout [B][N][heads][D]) to E4M3 codes in the SPARSE layout
  * [s*s*B][Nsub][heads][D] with one float32 scale per (subsequence, head, block of 128 consecutive positions):
  *   amax  = max |x| over the block (all D channels);  scale = amax / 448, inv = 448 / amax  (both float32; 1 if amax = 0)
