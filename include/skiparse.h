@@ -109,6 +109,25 @@ int skiparse_attn_fwd_sparse(const void* q, const void* k, const void* v, void* 
                              int head_dim, int s, int pattern, int out_layout, float scale, int dtype, void* stream);
 
 /*
+ * Training (Sec. 4.1: the model is fine-tuned with the sparse attention in place).
+ * skiparse_attn_fwd_lse: the fused forward (as skiparse_attn_fwd with SKIPARSE_FUSED) that also writes, for the backward pass,
+ *   lse[sb][head][j] = log sum_keys exp(scale q.k)  (natural log, float32, [s*s*B][heads][T*H*W/(s*s)]: subsequence order).
+ * skiparse_attn_bwd: gradients of that layer for a loss with dL/dout = dout:
+ *   dv = P^T dout,  dq = scale dS k,  dk = scale dS^T q,  dS = P o (dout v^T - rowsum(dout o out)),  P = exp(scale q k^T - lse),
+ *   all inside every subsequence.  q, k, v, out, dout, dq, dk, dv: ORIGINAL layout [B][T*H*W][heads][head_dim] bf16; out and lse
+ *   must be what skiparse_attn_fwd_lse produced for the same q, k, v, scale.  P and dS are rounded to bf16 for the matrix
+ *   products, accumulation is fp32, the gradients are rounded to bf16.  Deterministic (no atomics).
+ *   workspace: skiparse_bwd_workspace_bytes() bytes of device memory (one float per query and head).
+ *   No gradient buffer may overlap any other argument.  s = 1 gives the gradients of full attention.
+ */
+int skiparse_attn_fwd_lse(const void* q, const void* k, const void* v, void* out, float* lse, int B, int heads, int T, int H, int W,
+                          int head_dim, int s, int pattern, float scale, int dtype, void* stream);
+size_t skiparse_bwd_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern);
+int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
+                      void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
+                      int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * 8-bit variant (motivated by Sec. 3.5, which runs the attention MatMuls in an 8-bit format; here OCP fp8 e4m3
  * with fine-grained scales instead of per-tensor HiF8).
  * skiparse_quantize_fp8: x (bf16, ORIGINAL layout) -> x8 (e4m3fn bytes, SPARSE layout) and

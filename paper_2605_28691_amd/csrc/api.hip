@@ -198,6 +198,7 @@ int dense_attn_fwd(const void* q, const void* k, const void* v, void* out, int B
     a.g = make_dense_gridmap(sh.n_tok);
     a.pad = false;
     a.out_kind = OUT_AS_INPUT;
+    a.lse = nullptr;
     return finish(launch_attn_bf16(a, (hipStream_t)stream));
 }
 
@@ -228,6 +229,7 @@ int skiparse_attn_fwd(const void* q, const void* k, const void* v, void* out, in
     a.B = B; a.heads = heads; a.head_dim = head_dim;
     a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
     a.out_kind = OUT_AS_INPUT;
+    a.lse = nullptr;
     hipStream_t st = (hipStream_t)stream;
     if (flags & SKIPARSE_FUSED) {
         a.q = q; a.k = k; a.v = v; a.out = out;
@@ -284,8 +286,83 @@ int skiparse_attn_fwd_sparse(const void* q, const void* k, const void* v, void* 
     // with s = 1 every layout is the original one
     a.out_kind = (out_layout == SKIPARSE_OUT_SAME || s == 1) ? OUT_AS_INPUT : out_layout == SKIPARSE_OUT_ORIGINAL ? OUT_ORIGINAL : OUT_OTHER_PATTERN;
     a.out_B = B;
+    a.lse = nullptr;
     a.g_in = make_gridmap(T, H, W, s, pattern);
     return finish(launch_attn_bf16(a, (hipStream_t)stream));
+}
+
+int skiparse_attn_fwd_lse(const void* q, const void* k, const void* v, void* out, float* lse, int B, int heads, int T, int H, int W,
+                          int head_dim, int s, int pattern, float scale, int dtype, void* stream) {
+    Shape sh;
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
+    if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
+    const size_t bytes = sh.elems * 2, lse_bytes = (size_t)B * sh.n_tok * heads * sizeof(float);
+    rc = check_attn_ranges(sh, W, 2);
+    if (rc != SKIPARSE_OK) return rc;
+    rc = check_attn_ptrs(q, k, v, out, bytes);
+    if (rc != SKIPARSE_OK) return rc;
+    if (!lse || ((uintptr_t)lse & 3u)) return SKIPARSE_EINVAL;
+    if (overlap2(lse, lse_bytes, q, bytes) || overlap2(lse, lse_bytes, k, bytes) || overlap2(lse, lse_bytes, v, bytes) ||
+        overlap2(lse, lse_bytes, out, bytes))
+        return SKIPARSE_EINVAL;
+    AttnArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = out;
+    a.B = B; a.heads = heads; a.head_dim = head_dim;
+    a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+    a.g = make_gridmap(T, H, W, s, pattern);
+    a.pad = false;
+    a.out_kind = OUT_AS_INPUT;
+    a.lse = lse;
+    return finish(launch_attn_bf16(a, (hipStream_t)stream));
+}
+
+size_t skiparse_bwd_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern) {
+    Shape sh;
+    if (check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh) != SKIPARSE_OK) return 0;
+    return align256((size_t)B * sh.n_tok * heads * sizeof(float));
+}
+
+int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
+                      void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
+                      int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    Shape sh;
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
+    if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
+    const size_t bytes = sh.elems * 2, lse_bytes = (size_t)B * sh.n_tok * heads * sizeof(float);
+    rc = check_attn_ranges(sh, W, 2);
+    if (rc != SKIPARSE_OK) return rc;
+    const void* ins[5] = {q, k, v, out, dout};
+    void* outs[3] = {dq, dk, dv};
+    for (const void* x : ins)
+        if (!x || misaligned(x)) return SKIPARSE_EINVAL;
+    for (void* y : outs)
+        if (!y || misaligned(y)) return SKIPARSE_EINVAL;
+    if (!lse || ((uintptr_t)lse & 3u)) return SKIPARSE_EINVAL;
+    const size_t need = align256(lse_bytes);
+    if (!workspace || workspace_bytes < need || misaligned(workspace)) return SKIPARSE_EWORKSPACE;
+    // no gradient may alias an input, another gradient, the log-sum-exp or the workspace
+    for (int i = 0; i < 3; i++) {
+        for (const void* x : ins)
+            if (overlap(outs[i], x, bytes)) return SKIPARSE_EINVAL;
+        for (int j = i + 1; j < 3; j++)
+            if (overlap(outs[i], outs[j], bytes)) return SKIPARSE_EINVAL;
+        if (overlap2(outs[i], bytes, lse, lse_bytes) || overlap2(outs[i], bytes, workspace, need)) return SKIPARSE_EINVAL;
+    }
+    for (const void* x : ins)
+        if (overlap2(workspace, need, x, bytes)) return SKIPARSE_EINVAL;
+    if (overlap2(workspace, need, lse, lse_bytes)) return SKIPARSE_EINVAL;
+    BwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = out; a.dout = dout; a.lse = lse;
+    a.delta = (float*)workspace;
+    a.dq = dq; a.dk = dk; a.dv = dv;
+    a.B = B; a.heads = heads; a.head_dim = head_dim;
+    a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+    a.g = make_gridmap(T, H, W, s, pattern);
+    return finish(launch_attn_bwd_bf16(a, (hipStream_t)stream));
 }
 
 int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,

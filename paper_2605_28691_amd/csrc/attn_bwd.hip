@@ -1,0 +1,308 @@
+// bf16 flash-attention backward for gfx950 with the Skiparse row addressing folded in (the layer is fine-tuned, Sec. 4.1, so
+// it needs gradients).  For every attention unit (a subsequence and a head), with P = softmax(scale Q K^T) recomputed from
+// the forward's log-sum-exp L:
+//     delta_i = sum_d dO_id O_id                      (= sum_j P_ij dP_ij; one small kernel)
+//     dP = dO V^T,  dS = P o (dP - delta 1^T)
+//     dQ = scale dS K,   dK = scale dS^T Q,   dV = P^T dO
+// Three launches of one kernel template, each the forward kernel's scheme with the roles of the tensors exchanged: a lane
+// OWNS one row (a query for dQ, a key for dK and dV) whose operands stay in registers for the whole walk, and the rows of the
+// other side are STREAMED through LDS in tiles of 64:
+//     M1^T[streamed, owner] = A1 B1^T      (dQ: K Q^T;     dK, dV: Q K^T)        A1 from LDS, B1 = owner registers
+//     M2^T[streamed, owner] = A2 B2^T      (dQ: V dO^T;    dK: dO V^T;  dV: none)
+//     R = elementwise(M1, M2)              (dQ, dK: dS;    dV: P)                 registers, rounded to bf16
+//     acc^T[channel, owner] += A3^T R      (dQ: K^T dS^T;  dK: Q^T dS;  dV: dO^T P)   A3 read from LDS with the transposing read
+// As in the forward kernel the 32x32 accumulator layout gives every lane one owner column, so R's registers are directly the
+// B operand of the last product, and the owner's gradient row is accumulated in registers and written once: no atomics, the
+// result is deterministic.  dK and dV are separate launches because their accumulators together (128 registers) would not
+// leave room for two wavefronts per SIMD; the price is that S is recomputed once more (8 matrix products instead of 7).
+//   * log-sum-exp and delta are per QUERY: per-lane constants in the dQ launch, per-streamed-row values (staged in LDS next
+//     to the tile, +inf / 0 past the end so that such rows contribute nothing) in the other two.
+//   * A streamed tile that is read both ways is kept twice in LDS, once with the row stride that suits 16-byte fragment
+//     reads (D*2+16 bytes) and once with the stride that suits ds_read_b64_tr_b16 (D*2+64 bytes).
+//   * Rows are addressed through the Skiparse index map (Algorithm 1) exactly as in the forward kernel, so q, k, v, dO and the
+//     gradients are all in the original layout.
+#include "kernels.h"
+
+namespace skiparse {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+
+constexpr int BT = 64;             // streamed rows per tile
+constexpr int BNW = 8;             // wavefronts per workgroup: 256 owners share every streamed tile
+constexpr int BNT = 64 * BNW;
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int D, int MODE>
+__global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_tiles, uint32_t n_units) {
+    constexpr int KS = D / 16;   // MFMA steps along head_dim
+    constexpr int MT = D / 32;   // 32-channel blocks of the gradient row
+    constexpr int CH = D / 8;    // 16-byte chunks per row
+    constexpr int TPR = BNT / BT;        // threads staging one row
+    constexpr int CPT = CH / TPR;        // chunks per thread
+    constexpr int RS = D * 2 + 16;       // row stride for 16-byte fragment reads
+    constexpr int TS = D * 2 + 64;       // row stride for transposing reads
+    constexpr bool TWO = MODE != BWD_DV; // second product M2 present
+    constexpr int R1_BYTES = BT * RS, T_BYTES = BT * TS, R2_BYTES = TWO ? BT * RS : 0;
+    constexpr int BUF_BYTES = R1_BYTES + T_BYTES + R2_BYTES;
+    static_assert(CPT >= 1 && CPT * TPR == CH, "staging split");
+    __shared__ __attribute__((aligned(16))) char lds[2 * BUF_BYTES];
+    __shared__ __attribute__((aligned(16))) float row_l[2][BT];  // dK, dV: log2-domain log-sum-exp of the streamed queries
+    __shared__ __attribute__((aligned(16))) float row_d[2][BT];  // dK: their delta
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t lq = lane & 31u, h = lane >> 5;
+    const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
+    const uint32_t ul = idx / o_tiles, ot = idx - ul * o_tiles;
+    const uint32_t unit = ul * 8u + xcd;  // (subsequence or batch element) * heads + head
+    if (unit >= n_units) return;
+    const uint32_t bb = unit / (uint32_t)a.heads, head = unit - bb * (uint32_t)a.heads;
+    uint32_t p = 0, q = 0, b0 = bb;
+    if (a.g.mode != MODE_DENSE) {
+        const uint32_t pq = bb / (uint32_t)a.B;
+        b0 = bb - pq * (uint32_t)a.B;
+        p = pq / (uint32_t)a.g.s;
+        q = pq - p * (uint32_t)a.g.s;
+    }
+    const uint32_t n_seq = (uint32_t)a.g.n_sub;
+    const size_t C = (size_t)a.heads * D;
+    const size_t unit_off = (size_t)b0 * (uint32_t)a.g.n_tok * C + (size_t)head * D;  // elements
+    const float* lse_u = a.lse + (size_t)unit * n_seq;
+    const float* delta_u = a.delta + (size_t)unit * n_seq;
+
+    // tensors by role
+    const __bf16* own1_g = (const __bf16*)(MODE == BWD_DQ ? a.q : a.k) + unit_off;
+    const __bf16* own2_g = (const __bf16*)(MODE == BWD_DQ ? a.dout : a.v) + unit_off;
+    const char* st1_g = (const char*)((const __bf16*)(MODE == BWD_DQ ? a.k : a.q) + unit_off);
+    const char* st2_g = (const char*)((const __bf16*)(MODE == BWD_DQ ? a.v : a.dout) + unit_off);
+    __bf16* grad_g = (__bf16*)(MODE == BWD_DQ ? a.dq : MODE == BWD_DK ? a.dk : a.dv) + unit_off;
+
+    // ---- owner row: operands in registers (B operands: lane = owner lq, 8 consecutive channels starting at 16*ks + 8*h)
+    const uint32_t jo = ot * (32u * BNW) + wave * 32u + lq;
+    const bool own_valid = jo < n_seq;
+    const uint32_t jo_c = own_valid ? jo : n_seq - 1u;
+    const size_t own_off = (size_t)src_token(a.g, p, q, jo_c) * C;
+    bf16x8 own1[KS], own2[TWO ? KS : 1];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+        own1[ks] = *(const bf16x8*)(own1_g + own_off + ks * 16 + 8 * h);
+        if (TWO) own2[ks] = *(const bf16x8*)(own2_g + own_off + ks * 16 + 8 * h);
+    }
+    float own_l = 0.f, own_d = 0.f;  // dQ: the owner is a query
+    if (MODE == BWD_DQ) {
+        own_l = lse_u[jo_c] * LOG2E;
+        own_d = delta_u[jo_c];
+    }
+    const float c = a.scale * LOG2E;  // exp(x*scale - L) = exp2(x*c - L*log2e)
+
+    // ---- staging of streamed tiles: TPR threads per row, CPT consecutive 16-byte chunks each
+    const uint32_t st_row = tid / TPR, st_piece = tid % TPR;
+    u32x4 r1[CPT], r2[CPT];
+    float rl = 0.f, rd = 0.f;
+    auto load_tile = [&](uint32_t t) __attribute__((always_inline)) {
+        const uint32_t j = t * BT + st_row;
+        const size_t off = (size_t)src_token(a.g, p, q, j < n_seq ? j : n_seq - 1u) * C * 2 + (st_piece * CPT) * 16;  // bytes
+#pragma unroll
+        for (int i = 0; i < CPT; i++) {
+            r1[i] = *(const u32x4*)(st1_g + off + i * 16);
+            r2[i] = *(const u32x4*)(st2_g + off + i * 16);
+        }
+        if (MODE != BWD_DQ && tid < BT) {  // per-query values of the streamed rows; rows past the end contribute nothing
+            const uint32_t jj = t * BT + tid;
+            rl = jj < n_seq ? lse_u[jj] * LOG2E : INFINITY;
+            rd = (MODE == BWD_DK && jj < n_seq) ? delta_u[jj] : 0.f;
+        }
+    };
+    auto store_tile = [&](uint32_t buf) __attribute__((always_inline)) {
+        char* base = lds + buf * BUF_BYTES;
+#pragma unroll
+        for (int i = 0; i < CPT; i++) {
+            const uint32_t ch = (st_piece * CPT + i) * 16;
+            *(u32x4*)(base + st_row * RS + ch) = r1[i];
+            if (MODE != BWD_DV) *(u32x4*)(base + R1_BYTES + st_row * TS + ch) = r1[i];  // A3 = first streamed tensor
+            if (MODE == BWD_DV) *(u32x4*)(base + R1_BYTES + st_row * TS + ch) = r2[i];  // A3 = dO
+            if (TWO) *(u32x4*)(base + R1_BYTES + T_BYTES + st_row * RS + ch) = r2[i];
+        }
+        if (MODE != BWD_DQ && tid < BT) {
+            row_l[buf][tid] = rl;
+            row_d[buf][tid] = rd;
+        }
+    };
+
+    f32x16 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[mt][r] = 0.f;
+
+    const uint32_t a_rd = lq * RS + h * 16;  // + blk*32*RS + ks*32
+    // transposing read: a 16-lane group covers 4 rows x 16 channels; lane i of the group addresses row i/4, channels 4*(i%4)..
+    const uint32_t li = lane & 15u, lgrp = (lane >> 4) & 1u;
+    const uint32_t t_rd = (4 * h + (li >> 2)) * TS + (lgrp * 16 + 4 * (li & 3u)) * 2;  // + (blk*32 + m2*16 (+8))*TS + mt*64
+
+    const uint32_t n_t = (n_seq + BT - 1) / BT;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (uint32_t t = 0; t < n_t; t++) {
+        const bool more = t + 1 < n_t;
+        if (more) load_tile(t + 1);
+        const char* base = lds + (t & 1u) * BUF_BYTES;
+        const bool tail = MODE == BWD_DQ && !more && (n_seq % BT) != 0;  // dQ: streamed keys past the end are masked
+#pragma unroll
+        for (int blk = 0; blk < 2; blk++) {
+            f32x16 m1, m2;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                m1[r] = 0.f;
+                m2[r] = 0.f;
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+                const bf16x8 f1 = *(const bf16x8*)(base + a_rd + blk * 32 * RS + ks * 32);
+                m1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, own1[ks], m1, 0, 0, 0);
+            }
+            if (TWO) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) {
+                    const bf16x8 f2 = *(const bf16x8*)(base + R1_BYTES + T_BYTES + a_rd + blk * 32 * RS + ks * 32);
+                    m2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, own2[ks], m2, 0, 0, 0);
+                }
+            }
+            // register r of a block is streamed row 8*(r/4) + 4*h + r%4
+            f32x4 sl[4], sd[4];
+            if (MODE != BWD_DQ) {
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    sl[g] = *(const f32x4*)&row_l[t & 1u][blk * 32 + 8 * g + 4 * h];
+                    if (MODE == BWD_DK) sd[g] = *(const f32x4*)&row_d[t & 1u][blk * 32 + 8 * g + 4 * h];
+                }
+            }
+            bf16x8 rf[2];
+#pragma unroll
+            for (int g2 = 0; g2 < 2; g2++) {
+                bf16x8 pk;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    f32x2 val;
+#pragma unroll
+                    for (int u = 0; u < 2; u++) {
+                        const int r = g2 * 8 + e + u;
+                        const float l2 = MODE == BWD_DQ ? own_l : sl[r >> 2][r & 3];
+                        float pr = __builtin_amdgcn_exp2f(fmaf(m1[r], c, -l2));
+                        if (tail) {
+                            const uint32_t row = t * BT + blk * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                            pr = row < n_seq ? pr : 0.f;
+                        }
+                        if (MODE == BWD_DV) val[u] = pr;
+                        else val[u] = pr * (m2[r] - (MODE == BWD_DQ ? own_d : sd[r >> 2][r & 3]));
+                    }
+                    const bf16x2 vb = __builtin_convertvector(val, bf16x2);
+                    pk[e] = vb[0];
+                    pk[e + 1] = vb[1];
+                }
+                rf[g2] = pk;
+            }
+#pragma unroll
+            for (int g2 = 0; g2 < 2; g2++)
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) {
+                    const char* ta = base + R1_BYTES + t_rd + (blk * 32 + g2 * 16) * TS + mt * 64;
+                    const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))ta);
+                    const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + 8 * TS));
+                    const bf16x8 tf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, rf[g2], acc[mt], 0, 0, 0);
+                }
+        }
+        if (more) store_tile((t + 1) & 1u);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane owns row jo; register r of block mt is channel 32*mt + 8*(r/4) + 4*h + r%4
+    if (own_valid) {
+        const float f = MODE == BWD_DV ? 1.0f : a.scale;
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; e++) o[e] = (__bf16)(acc[mt][g * 4 + e] * f);
+                *(bf16x4*)(grad_g + own_off + mt * 32 + g * 8 + 4 * h) = o;
+            }
+    }
+}
+
+// delta[unit][j] = sum_d dO[row][head][d] * O[row][head][d]: one wavefront per position (sb, j), D/8 lanes per head.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
+                                                        float* __restrict__ delta, GridMap g, int B, int heads, uint32_t n_rows) {
+    constexpr int LPH = D / 8;        // lanes per head (16 bytes each)
+    constexpr int HPP = 64 / LPH;     // heads per pass
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t row = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const uint32_t n_sub = (uint32_t)g.n_sub;
+    const uint32_t sb = row / n_sub, j = row - sb * n_sub;
+    uint32_t p = 0, q = 0, b0 = sb;
+    if (g.mode != MODE_DENSE) {
+        const uint32_t pq = sb / (uint32_t)B;
+        b0 = sb - pq * (uint32_t)B;
+        p = pq / (uint32_t)g.s;
+        q = pq - p * (uint32_t)g.s;
+    }
+    const size_t C = (size_t)heads * D;
+    const size_t base = ((size_t)b0 * (uint32_t)g.n_tok + src_token(g, p, q, j)) * C;
+    for (uint32_t h0 = 0; h0 < (uint32_t)heads; h0 += HPP) {
+        const uint32_t head = h0 + lane / LPH;
+        float sum = 0.f;
+        if (head < (uint32_t)heads) {
+            const size_t off = base + (size_t)head * D + (lane % LPH) * 8;
+            const bf16x8 o = *(const bf16x8*)(out + off);
+            const bf16x8 d = *(const bf16x8*)(dout + off);
+#pragma unroll
+            for (int e = 0; e < 8; e++) sum = fmaf((float)o[e], (float)d[e], sum);
+        }
+#pragma unroll
+        for (int m = LPH / 2; m >= 1; m >>= 1) sum += __shfl_xor(sum, m);
+        if (head < (uint32_t)heads && lane % LPH == 0) delta[((size_t)sb * heads + head) * n_sub + j] = sum;
+    }
+}
+
+template <int D, int MODE>
+static hipError_t launch_mode(const BwdArgs& a, hipStream_t stream) {
+    const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
+    const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
+    const uint32_t o_tiles = ((uint32_t)a.g.n_sub + 32u * BNW - 1u) / (32u * BNW);
+    const uint64_t blocks = (uint64_t)((n_units + 7u) / 8u * 8u) * o_tiles;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    attn_bwd_kernel<D, MODE><<<(uint32_t)blocks, BNT, 0, stream>>>(a, o_tiles, n_units);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_all(const BwdArgs& a, hipStream_t stream) {
+    const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
+    const uint32_t n_rows = (uint32_t)a.B * s2 * (uint32_t)a.g.n_sub;
+    bwd_delta_kernel<D><<<(n_rows + 3u) / 4u, 256, 0, stream>>>((const __bf16*)a.out, (const __bf16*)a.dout, a.delta, a.g, a.B, a.heads, n_rows);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if ((e = launch_mode<D, BWD_DQ>(a, stream)) != hipSuccess) return e;
+    if ((e = launch_mode<D, BWD_DK>(a, stream)) != hipSuccess) return e;
+    return launch_mode<D, BWD_DV>(a, stream);
+}
+
+hipError_t launch_attn_bwd_bf16(const BwdArgs& a, hipStream_t stream) {
+    if (a.head_dim == 128) return launch_all<128>(a, stream);
+    if (a.head_dim == 64) return launch_all<64>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace skiparse

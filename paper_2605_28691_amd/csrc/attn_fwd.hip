@@ -548,6 +548,11 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         float llo, lhi;
         lane_pair(l_run[qi], llo, lhi);
         const float inv = 1.0f / (llo + lhi);
+        if (a.lse != nullptr && h == 0) {
+            // log-sum-exp of the scaled logits: the reference is in raw logit units, the sum is relative to it
+            const uint32_t jq = qt * BR + (wave * QT + qi) * 32u + lq;
+            if (jq < n_seq) a.lse[(size_t)unit * n_seq + jq] = q_valid[qi] ? m_ref[qi] * a.scale + __logf(llo + lhi) : 0.f;
+        }
         if (q_valid[qi]) {
             __bf16* orow = Og + q_row_off[qi];
             if (a.out_kind != OUT_AS_INPUT) {

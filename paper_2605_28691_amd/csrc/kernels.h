@@ -34,12 +34,34 @@ struct AttnArgs {
     // Where the output rows go.  OUT_AS_INPUT: out is addressed like q.  OUT_ORIGINAL / OUT_OTHER_PATTERN: q, k, v are the
     // sparse layout of pattern g_in (so g is a dense map over its B*s*s subsequences) and the row of query (sb, j) is written
     // at its place in the original layout / in the sparse layout of the other pattern (Alg. 1, tsa_to_gsa / gsa_to_tsa).
+    float* lse;     // optional: natural-log log-sum-exp of the scaled logits of every query, [unit][position] (for the backward pass)
     int out_kind;
     int out_B;      // batch elements of the original layout (only for out_kind != OUT_AS_INPUT)
     GridMap g_in;   // index map of the input's pattern (only for out_kind != OUT_AS_INPUT)
 };
 enum OutKind : int { OUT_AS_INPUT = 0, OUT_ORIGINAL = 1, OUT_OTHER_PATTERN = 2 };
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
+
+// Flash-attention backward, bf16: delta = rowsum(dO o O), then dQ, dK and dV (one launch each).  Addressing as in AttnArgs.
+enum BwdMode : int { BWD_DQ = 0, BWD_DV = 1, BWD_DK = 2 };
+struct BwdArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const void* out;    // the forward's output
+    const void* dout;   // gradient of the loss with respect to it
+    const float* lse;   // the forward's log-sum-exp, [unit][position]
+    float* delta;       // workspace, [unit][position]
+    void* dq;
+    void* dk;
+    void* dv;
+    int B;
+    int heads;
+    int head_dim;
+    float scale;
+    GridMap g;
+};
+hipError_t launch_attn_bwd_bf16(const BwdArgs& a, hipStream_t stream);
 
 // bf16 (original layout) -> E4M3 codes (sparse layout) + one float32 scale per (subsequence, head, 128 positions).
 hipError_t launch_quantize_fp8(const void* x, void* x8, float* scales, int B, int heads, int head_dim, const GridMap& g,

@@ -92,6 +92,16 @@ def make_qkv(w: Workload):
     return tuple(out)
 
 
+def make_dout(w: Workload) -> torch.Tensor:
+    """Upstream gradient dL/dout for the backward pass: N(0,1) in the workload's storage dtype, seeded apart from q, k, v."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed + 1000)
+    x = torch.randn((w.B, w.N, w.heads, w.D), generator=g, dtype=torch.float32)
+    if w.dtype == "bf16":
+        x = x.to(torch.bfloat16)
+    return x.contiguous()
+
+
 def as_oracle_array(x: torch.Tensor) -> np.ndarray:
     """View a CPU tensor as what the oracle takes: float32/float64 as is, bfloat16 as uint16 bit patterns."""
     if x.dtype == torch.bfloat16:

@@ -1,0 +1,143 @@
+"""GPU parity: skiparse_attn_fwd_lse + skiparse_attn_bwd through the C ABI against the float64 oracle's gradients.
+
+Tolerance (bf16 path: P and dS rounded to bf16 for the matrix products, fp32 accumulation, bf16 results), per gradient:
+relative L2 error <= 1e-2 and max |diff| <= 3e-2 * max |reference|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from _util import errors, oracle_inputs, to_np64
+
+pytestmark = pytest.mark.gpu
+
+BWD_REL_L2 = 1e-2
+BWD_MAX_REL = 3e-2
+
+SMALL = [  # B, heads, D, T, H, W, s
+    (1, 2, 64, 2, 8, 8, 2),      # 32 tokens per subsequence: a single partial tile on both sides
+    (2, 3, 128, 3, 8, 12, 2),    # Nsub = 72: one full + one partial streamed tile
+    (1, 2, 128, 5, 16, 20, 2),   # Nsub = 400: two owner tiles (256 + 144), 7 streamed tiles with a tail of 16
+    (2, 2, 64, 5, 16, 20, 2),    # head_dim 64, batch of 2
+    (1, 9, 128, 4, 9, 18, 3),    # s = 3, 9 heads
+    (1, 2, 128, 7, 16, 16, 2),   # Nsub = 448 = 7 * 64: no tail
+]
+
+
+def assert_grad_close(got, want, what):
+    assert np.isfinite(got).all(), f"{what}: non-finite"
+    max_abs, rel_l2 = errors(got, want)
+    lim = BWD_MAX_REL * float(np.abs(want).max())
+    assert rel_l2 <= BWD_REL_L2 and max_abs <= lim, f"{what}: rel-L2 {rel_l2:.3e}, max-abs {max_abs:.3e} (limit {lim:.3e})"
+    return max_abs, rel_l2
+
+
+def _run(sk, q, k, v, dout, T, H, W, s, pattern, scale):
+    qg, kg, vg, dg = (t.cuda() for t in (q, k, v, dout))
+    out, lse = sk.skiparse_attn_fwd_lse(qg, kg, vg, T, H, W, s, pattern, scale=scale)
+    dq, dk, dv = sk.skiparse_attn_bwd(qg, kg, vg, out, dg, lse, T, H, W, s, pattern, scale=scale)
+    return out, lse, dq, dk, dv
+
+
+@pytest.mark.parametrize("B,heads,D,T,H,W,s", SMALL)
+@pytest.mark.parametrize("pattern", ["token", "group"])
+def test_backward_small(B, heads, D, T, H, W, s, pattern):
+    import paper_2605_28691_amd as sk
+
+    if pattern == "group" and (H % (s * s) or W % (s * s)):
+        pytest.skip("group-wise needs multiples of s^2")
+    w = si.make_shape("bwd", B, heads, D, T, H, W, s, seed=40 + s)
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    want = oracle.skiparse_attention_bwd(*oracle_inputs(q, k, v), si.as_oracle_array(dout), T, H, W, s, pattern, w.scale)
+    out, lse, dq, dk, dv = _run(sk, q, k, v, dout, T, H, W, s, pattern, w.scale)
+    # the forward with the extra output is the same forward
+    assert torch.equal(out, sk.skiparse_attn_fwd(q.cuda(), k.cuda(), v.cuda(), T, H, W, s, pattern, scale=w.scale))
+    # log-sum-exp against its definition on the rearranged tensors (float64)
+    qs, ks = (oracle.permute(to_np64(t), T, H, W, s, pattern) for t in (q, k))
+    logits = np.einsum("bihd,bjhd->bhij", qs, ks) * w.scale
+    m = logits.max(-1, keepdims=True)
+    lse_ref = (m + np.log(np.exp(logits - m).sum(-1, keepdims=True)))[..., 0]
+    assert np.abs(to_np64(lse) - lse_ref).max() <= 5e-3
+    for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+        assert_grad_close(to_np64(g), wnt, f"{pattern} {name}")
+
+
+@pytest.mark.parametrize("B,heads,D,N", [(1, 2, 128, 1000), (2, 3, 64, 333), (1, 1, 128, 64), (1, 1, 64, 1)])
+def test_backward_dense_s1(B, heads, D, N):
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("bwd_dense", B, heads, D, 1, 1, N, 1, seed=N + 1)
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    want = oracle.attention_bwd(*oracle_inputs(q, k, v), si.as_oracle_array(dout), w.scale)
+    _, _, dq, dk, dv = _run(sk, q, k, v, dout, 1, 1, N, 1, "token", w.scale)
+    for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+        if N == 1:  # one key: dv = dout exactly, dq = dk = 0
+            assert np.abs(to_np64(g) - wnt).max() <= 1e-6, name
+        else:
+            assert_grad_close(to_np64(g), wnt, f"dense {name}")
+
+
+def test_backward_peaky_logits():
+    """Large logits (one dominant key per query): P is nearly one-hot and the log-sum-exp is large."""
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("bwd_peaky", 1, 2, 128, 2, 8, 16, 2, seed=3)
+    q, k, v = si.make_qkv(w)
+    q, k = (q.float() * 4.0).to(torch.bfloat16), (k.float() * 4.0).to(torch.bfloat16)
+    dout = si.make_dout(w)
+    want = oracle.skiparse_attention_bwd(*oracle_inputs(q, k, v), si.as_oracle_array(dout), w.T, w.H, w.W, w.s, "token", w.scale)
+    _, _, dq, dk, dv = _run(sk, q, k, v, dout, w.T, w.H, w.W, w.s, "token", w.scale)
+    for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+        assert_grad_close(to_np64(g), wnt, f"peaky {name}")
+
+
+def test_backward_is_deterministic_and_stays_in_bounds():
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("bwd_det", 1, 3, 128, 3, 8, 12, 2, seed=8)
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    qg, kg, vg, dg = (t.cuda() for t in (q, k, v, dout))
+    out, lse = sk.skiparse_attn_fwd_lse(qg, kg, vg, w.T, w.H, w.W, w.s, "group", scale=w.scale)
+    n = q.numel()
+    pad = 4096
+    runs = []
+    for _ in range(2):
+        buf = torch.full((3, n + 2 * pad), 7.0, dtype=torch.bfloat16, device="cuda")  # canaries around every gradient
+        views = [buf[i, pad : pad + n].view(q.shape) for i in range(3)]
+        sk.skiparse_attn_bwd(qg, kg, vg, out, dg, lse, w.T, w.H, w.W, w.s, "group", scale=w.scale, dq=views[0], dk=views[1], dv=views[2])
+        assert bool((buf[:, :pad] == 7.0).all()) and bool((buf[:, pad + n :] == 7.0).all())
+        runs.append(buf)
+    assert torch.equal(runs[0], runs[1])
+
+
+def test_backward_480p_one_unit_and_invariants():
+    """Benchmark-shaped grid: the gradients of sampled tokens of one attention unit against the oracle (which walks the whole
+    unit), plus properties that hold at any size for every unit: sum_keys dk = 0 and sum_keys dv = sum_queries dout."""
+    import paper_2605_28691_amd as sk
+
+    w = si.WORKLOADS["480p"]
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    T, H, W, s = w.T, w.H, w.W, w.s
+    _, _, dq, dk, dv = _run(sk, q, k, v, dout, T, H, W, s, "token", w.scale)
+    b, head, n0 = 0, 5, 12345
+    p0, q0, _ = oracle.dst_index("token", s, T, H, W, n0)
+    toks = [n0] + [oracle.src_index("token", s, T, H, W, p0, q0, j) for j in (0, 1, 4097, w.Nsub - 1)]
+    want = oracle.skiparse_attention_bwd_unit(*oracle_inputs(q, k, v), si.as_oracle_array(dout), b, head, toks, T, H, W, s, "token", w.scale)
+    for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+        assert_grad_close(to_np64(g[b, toks, head]), wnt, f"480p {name}")
+    # invariants per (batch, head, subsequence), in float64 on the bf16 results
+    for pattern_class in range(s * s):
+        p, qq = divmod(pattern_class, s)
+        idx = torch.tensor([oracle.src_index("token", s, T, H, W, p, qq, j) for j in range(0, w.Nsub)], device="cuda")
+        dk_sum = dk[0, idx].double().sum(0)                     # [heads][D]
+        dv_sum = dv[0, idx].double().sum(0)
+        do_sum = dout.cuda()[0, idx].double().sum(0)
+        dk_abs = dk[0, idx].double().abs().sum(0)
+        assert float((dk_sum.abs() / dk_abs).max()) <= 2e-2     # cancels up to the bf16 rounding of the rows
+        assert float((dv_sum - do_sum).abs().max()) <= 2e-2 * float(do_sum.abs().max())
