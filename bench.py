@@ -54,8 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="768p", choices=["480p", "768p"])
     ap.add_argument("--cpu-rows", type=int, default=16384, help="query rows the oracle computes for cpu_baseline")
     ap.add_argument("--skip-extras", action="store_true", help="only the headline timing (used under the profiler)")
-    ap.add_argument("--extras", default="group,unfused,permute,chain,dense,fp8,pad,cpu",
-                    help="comma list of the extra sections to run: group, unfused, permute, chain (sparse layout in, other pattern's layout out), dense, fp8, pad (720P-shaped grid in the "
+    ap.add_argument("--extras", default="group,unfused,permute,chain,bwd,dense,fp8,pad,cpu",
+                    help="comma list of the extra sections to run: group, unfused, permute, chain (sparse layout in, other pattern's layout out), bwd (backward pass), dense, fp8, pad (720P-shaped grid in the "
                          "any-resolution mode), cpu (oracle baseline + parity)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -176,6 +176,20 @@ def main() -> int:
         extras["chain_token_to_group_ms"] = round(c_ms, 4)
         extras["chain_token_to_group_tflops"] = round(flops / c_ms / 1e9, 2)
         del qs, ks, vs, os_
+    if "bwd" in sections:
+        # training step of the layer: forward that keeps the log-sum-exp, then dQ, dK, dV (delta + three launches)
+        dout = si.make_dout(w).cuda()
+        lse = torch.empty((s * s * w.B, w.heads, w.Nsub), dtype=torch.float32, device="cuda")
+        grads = [torch.empty_like(qd) for _ in range(3)]
+        wsb = torch.empty(sk.skiparse_bwd_workspace_bytes(w.B, w.heads, T, H, W, w.D, s, "token"), dtype=torch.uint8, device="cuda")
+        fl_ms = time_calls(lambda: sk.skiparse_attn_fwd_lse(qd, kd, vd, T, H, W, s, "token", scale=w.scale, out=out, lse=lse), it, 1)
+        b_ms = time_calls(lambda: sk.skiparse_attn_bwd(qd, kd, vd, out, dout, lse, T, H, W, s, "token", scale=w.scale, dq=grads[0], dk=grads[1],
+                                                       dv=grads[2], workspace=wsb), 3, 1)
+        extras["fwd_lse_ms"] = round(fl_ms, 4)
+        extras["bwd_ms"] = round(b_ms, 4)
+        extras["bwd_effective_tflops"] = round(2.5 * flops / b_ms / 1e9, 2)  # five matrix products of the definition (forward has two)
+        extras["bwd_executed_tflops"] = round(4.0 * flops / b_ms / 1e9, 2)   # eight are executed (S is recomputed in each launch)
+        del dout, lse, grads, wsb
     if "dense" in sections:
         d_ms = time_calls(lambda: sk.dense_attn_fwd(qd, kd, vd, T, H, W, scale=w.scale, out=out), 3, 1)
         extras["dense_ms"] = round(d_ms, 4)
