@@ -54,8 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="768p", choices=["480p", "768p"])
     ap.add_argument("--cpu-rows", type=int, default=16384, help="query rows the oracle computes for cpu_baseline")
     ap.add_argument("--skip-extras", action="store_true", help="only the headline timing (used under the profiler)")
-    ap.add_argument("--extras", default="group,unfused,permute,chain,bwd,dense,fp8,pad,cpu",
-                    help="comma list of the extra sections to run: group, unfused, permute, chain (sparse layout in, other pattern's layout out), bwd (backward pass), dense, fp8, pad (720P-shaped grid in the "
+    ap.add_argument("--extras", default="probe,group,unfused,permute,chain,bwd,dense,fp8,pad,cpu",
+                    help="comma list of the extra sections to run: probe (MFMA-only kernel: attainable matrix throughput), group, unfused, permute, chain (sparse layout in, other pattern's layout out), bwd (backward pass), dense, fp8, pad (720P-shaped grid in the "
                          "any-resolution mode), cpu (oracle baseline + parity)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -136,8 +136,36 @@ def main() -> int:
         "input_generation_s": round(gen_s, 1),
     }
 
+    props = torch.cuda.get_device_properties(0)
+    clock_khz = getattr(props, "clock_rate", None)
+    result["device"] = {
+        "name": props.name,
+        "compute_units": props.multi_processor_count,
+        "clock_mhz": round(clock_khz / 1e3, 1) if clock_khz else None,
+        # 4 SIMDs x 1024 bf16 FLOP per clock per compute unit (one 32x32x16 MFMA = 32768 FLOP in 32 clocks per SIMD)
+        "bf16_tflops_from_device": round(props.multi_processor_count * 4096 * clock_khz / 1e9, 1) if clock_khz else None,
+    }
+
     sections = set() if args.skip_extras else {x for x in args.extras.split(",") if x}
     extras = {}
+    if "probe" in sections:
+        # what the matrix pipe sustains by itself on random operands (power-managed clock): nothing but MFMAs, 8 wavefronts per SIMD
+        gp = torch.Generator(device="cpu")
+        gp.manual_seed(99)
+        rnd = torch.randn(8192, generator=gp, dtype=torch.float32)
+        sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+        for name, ops, fp8, n_it in (("bf16", rnd.to(torch.bfloat16).cuda(), False, 20000),
+                                     ("fp8", rnd.repeat(2).to(torch.float8_e4m3fn).view(torch.uint8).cuda(), True, 10000),
+                                     ("bf16_zero_operands", torch.zeros(8192, dtype=torch.bfloat16, device="cuda"), False, 20000)):
+            fl = [0.0]
+
+            def probe():
+                fl[0] = sk.skiparse_mfma_probe(ops, sink, fp8, 2048, n_it)
+
+            p_ms = time_calls(probe, 5, 2)
+            extras[f"mfma_only_{name}_tflops"] = round(fl[0] / p_ms / 1e9, 1)
+        result["roofline"]["attainable_mfma_only"] = extras["mfma_only_bf16_tflops"]
+        del sink
     it = max(3, min(10, args.steps))
     out8 = None
     tensor_bytes = qd.numel() * 2

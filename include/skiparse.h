@@ -147,6 +147,17 @@ int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const 
                           void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
                           float scale, void* stream);
 
+/*
+ * Measurement aid, not part of the method: enqueues a kernel that issues nothing but matrix-core instructions (32x32x16 bf16
+ * for SKIPARSE_BF16, 32x32x64 fp8 for SKIPARSE_FP8_E4M3) on the caller's operand bytes, `blocks` workgroups of 4 wavefronts,
+ * iters * 4 instructions per wavefront.  The benchmark times it to report what the matrix pipe sustains by itself on the
+ * same kind of data (the clock is power-managed), next to the nominal peak.  operands: >= 2048 * 8 bytes of device memory
+ * (random values of the element type); sink: >= blocks * 256 floats, overwritten.  *flop (host pointer, may be NULL) receives
+ * the floating-point operations of one launch.
+ */
+int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int dtype, int blocks, int iters,
+                        double* flop, void* stream);
+
 /* Text for an error code; never NULL. */
 const char* skiparse_strerror(int code);
 

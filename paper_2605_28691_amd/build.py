@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libskiparse.so")
-SOURCES = ["api.hip", "permute.hip", "attn_fwd.hip", "attn_bwd.hip", "quant_fp8.hip", "attn_fwd_fp8.hip"]
+SOURCES = ["api.hip", "permute.hip", "attn_fwd.hip", "attn_bwd.hip", "quant_fp8.hip", "attn_fwd_fp8.hip", "mfma_probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950",
     "-O3",

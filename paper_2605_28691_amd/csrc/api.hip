@@ -401,6 +401,17 @@ int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const 
     return finish(launch_attn_fp8(a, (hipStream_t)stream));
 }
 
+int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int dtype, int blocks, int iters,
+                        double* flop, void* stream) {
+    if (!operands || !sink || misaligned(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (dtype != SKIPARSE_BF16 && dtype != SKIPARSE_FP8_E4M3) return SKIPARSE_EUNSUPPORTED;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    const double per_mfma = dtype == SKIPARSE_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 64;
+    if (flop) *flop = per_mfma * 4.0 /* per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
+    return finish(launch_mfma_probe(operands, sink, dtype == SKIPARSE_FP8_E4M3, blocks, iters, (hipStream_t)stream));
+}
+
 const char* skiparse_strerror(int code) {
     switch (code) {
         case SKIPARSE_OK: return "ok";

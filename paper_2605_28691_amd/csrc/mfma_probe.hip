@@ -1,0 +1,58 @@
+// Measurement aid: a loop of nothing but matrix-core instructions on caller-supplied operands.  It shows what the matrix pipe
+// of this chip sustains by itself under the board's power management (on random operands the clock drops well below nominal),
+// which is the ceiling the attention kernels are judged against besides the nominal peak.
+#include "kernels.h"
+
+namespace skiparse {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+constexpr int PROBE_THREADS = 256;  // 4 wavefronts, one per SIMD; several workgroups share a compute unit
+constexpr int PROBE_FRAGS = 4;      // operand pairs cycled through, so that consecutive MFMAs see different data
+
+// operands: at least PROBE_FRAGS * 2 * 64 * 32 bytes of arbitrary (e.g. random bf16 / e4m3) data
+template <bool FP8>
+__global__ __launch_bounds__(PROBE_THREADS) void mfma_probe_kernel(const char* __restrict__ operands, float* __restrict__ sink, int iters) {
+    const uint32_t lane = threadIdx.x & 63u;
+    i32x8 a[PROBE_FRAGS], b[PROBE_FRAGS];  // 32 bytes per lane each; the bf16 instruction uses the first 16
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++) {
+        a[f] = *(const i32x8*)(operands + ((size_t)(2 * f) * 64 + lane) * 32);
+        b[f] = *(const i32x8*)(operands + ((size_t)(2 * f + 1) * 64 + lane) * 32);
+    }
+    f32x16 acc[PROBE_FRAGS];
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[f][r] = 0.f;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int f = 0; f < PROBE_FRAGS; f++) {
+            if (FP8) {
+                acc[f] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[f], b[(f + 1) % PROBE_FRAGS], acc[f], 0, 0, 0, 0, 0, 0);
+            } else {
+                const bf16x8 av = __builtin_bit_cast(bf16x8, __builtin_shufflevector(a[f], a[f], 0, 1, 2, 3));
+                const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_shufflevector(b[(f + 1) % PROBE_FRAGS], b[(f + 1) % PROBE_FRAGS], 0, 1, 2, 3));
+                acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[f], 0, 0, 0);
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) s += acc[f][r];
+    sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
+}
+
+hipError_t launch_mfma_probe(const void* operands, float* sink, int fp8, int blocks, int iters, hipStream_t stream) {
+    if (fp8)
+        mfma_probe_kernel<true><<<blocks, PROBE_THREADS, 0, stream>>>((const char*)operands, sink, iters);
+    else
+        mfma_probe_kernel<false><<<blocks, PROBE_THREADS, 0, stream>>>((const char*)operands, sink, iters);
+    return hipGetLastError();
+}
+
+}  // namespace skiparse

@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
-            "skiparse_switch_pattern", "skiparse_attn_fwd_sparse"} <= set(names)
+            "skiparse_switch_pattern", "skiparse_attn_fwd_sparse", "skiparse_attn_fwd_lse",
+            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_mfma_probe"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -148,3 +149,39 @@ def test_attn_fwd_sparse_rejects_bad_arguments(lib):
     assert call(12, 12, 2, 0, 0, out=None) == -1
     assert call(12, 12, 2, 0, 0, D=96) == -3    # no kernel for this head_dim
     assert call(12, 12, 2, 0, 0, dtype=1) == -3  # bf16 only
+
+
+def test_backward_rejects_bad_arguments(lib):
+    a = [ctypes.c_void_p(FAKE + i * (1 << 30)) for i in range(11)]
+    f = ctypes.c_float(0.0)
+    need = lib.skiparse_bwd_workspace_bytes(1, 2, 2, 8, 8, 64, 2, 0)
+    assert need == 1 * 128 * 2 * 4  # one float per query and head (already a multiple of 256)
+    assert lib.skiparse_bwd_workspace_bytes(1, 2, 2, 7, 8, 64, 2, 0) == 0  # bad shape
+
+    def bwd(ptrs, ws=a[9], ws_bytes=need, H=8, D=64, dtype=0):
+        return lib.skiparse_attn_bwd(*ptrs, 1, 2, 2, H, 8, D, 2, 0, f, dtype, ws, ws_bytes, None)
+
+    ok = a[:9]
+    assert bwd([None] + ok[1:]) == -1
+    assert bwd(ok[:6] + [ok[0]] + ok[7:]) == -1        # dq aliases q
+    assert bwd(ok[:7] + [ok[6]] + ok[8:]) == -1        # dk aliases dq
+    assert bwd(ok, ws=None) == -4
+    assert bwd(ok, ws_bytes=need - 1) == -4
+    assert bwd(ok, ws=ok[8]) == -1                     # workspace aliases dv
+    assert bwd(ok, H=7) == -2
+    assert bwd(ok, D=96) == -3
+    assert bwd(ok, dtype=1) == -3
+    # forward with log-sum-exp
+    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], None, 1, 2, 2, 8, 8, 64, 2, 0, f, 0, None) == -1
+    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], a[3], 1, 2, 2, 8, 8, 64, 2, 0, f, 0, None) == -1  # lse aliases out
+    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], a[4], 1, 2, 2, 8, 6, 64, 2, 1, f, 0, None) == -2  # group-wise needs W % 4 == 0
+
+
+def test_mfma_probe_rejects_bad_arguments(lib):
+    p, q = ctypes.c_void_p(FAKE), ctypes.c_void_p(FAKE + (1 << 30))
+    flop = ctypes.c_double(0.0)
+    assert lib.skiparse_mfma_probe(None, 1 << 20, q, 1 << 30, 0, 8, 10, ctypes.byref(flop), None) == -1
+    assert lib.skiparse_mfma_probe(p, 1 << 20, q, 1 << 30, 1, 8, 10, ctypes.byref(flop), None) == -3   # fp32: no such probe
+    assert lib.skiparse_mfma_probe(p, 100, q, 1 << 30, 0, 8, 10, ctypes.byref(flop), None) == -4       # operand buffer too small
+    assert lib.skiparse_mfma_probe(p, 1 << 20, q, 8 * 256 * 4 - 1, 0, 8, 10, ctypes.byref(flop), None) == -4
+    assert lib.skiparse_mfma_probe(p, 1 << 20, q, 1 << 30, 0, 0, 10, ctypes.byref(flop), None) == -1

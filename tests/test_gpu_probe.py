@@ -1,0 +1,24 @@
+"""GPU: the MFMA-only measurement kernel runs, reports its FLOP count and writes the sums of its accumulators."""
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def test_mfma_probe_runs_and_counts_flop():
+    import paper_2605_28691_amd as sk
+
+    ops = torch.zeros(8192, dtype=torch.bfloat16, device="cuda")
+    ops[:] = 1.0  # every product is 1: an accumulator element after n MFMAs of depth 16 is 16 n
+    sink = torch.full((16 * 256,), -1.0, dtype=torch.float32, device="cuda")
+    flop = sk.skiparse_mfma_probe(ops, sink, False, 16, 3)
+    torch.cuda.synchronize()
+    assert flop == 2.0 * 32 * 32 * 16 * 4 * 3 * 4 * 16
+    # each thread sums 4 accumulators x 16 registers, every register = 16 * 3
+    assert bool((sink == 4 * 16 * 16 * 3).all())
+    # fp8: 0x38 is 1.0 in E4M3; depth 64
+    ops8 = torch.full((16384,), 0x38, dtype=torch.uint8, device="cuda")
+    flop8 = sk.skiparse_mfma_probe(ops8, sink, True, 16, 2)
+    torch.cuda.synchronize()
+    assert flop8 == 2.0 * 32 * 32 * 64 * 4 * 2 * 4 * 16
+    assert bool((sink == 4 * 16 * 64 * 2).all())
