@@ -89,15 +89,16 @@ def main() -> int:
     for _ in range(args.warmup):
         fused("token")()
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # on the stream the kernels are launched on
     wall0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
+    evs[0].record()
+    for i in range(args.steps):
         fused("token")()
-    ev1.record()
+        evs[i + 1].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - wall0) * 1e3 / args.steps
-    kernel_ms = ev0.elapsed_time(ev1) / args.steps  # one kernel per step: this is the kernel's average duration
+    kernel_ms = evs[0].elapsed_time(evs[-1]) / args.steps  # one kernel per step: this is the kernel's average duration
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
     ms = wall_ms
     tflops = flops / (ms * 1e-3) / 1e12
     result = {
@@ -131,6 +132,8 @@ def main() -> int:
             "algorithmic_bytes": 4 * qd.numel() * 2,
             "kernel": "attn_fwd_bf16_kernel<128>",
             "kernel_ms": round(kernel_ms, 4),
+            "kernel_ms_min": round(per_step[0], 4),
+            "kernel_ms_median": round(per_step[len(per_step) // 2], 4),
         },
         "paper_context": PAPER_CONTEXT,
         "input_generation_s": round(gen_s, 1),
