@@ -41,7 +41,7 @@ constexpr int BNT = 64 * BNW;
 constexpr float LOG2E = 1.4426950408889634f;
 
 template <int D, int MODE>
-__global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_tiles, uint32_t n_units) {
+__global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_tiles, uint32_t total, uint32_t per_xcd) {
     constexpr int KS = D / 16;   // MFMA steps along head_dim
     constexpr int MT = D / 32;   // 32-channel blocks of the gradient row
     constexpr int CH = D / 8;    // 16-byte chunks per row
@@ -60,9 +60,9 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t lq = lane & 31u, h = lane >> 5;
     const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
-    const uint32_t ul = idx / o_tiles, ot = idx - ul * o_tiles;
-    const uint32_t unit = ul * 8u + xcd;  // (subsequence or batch element) * heads + head
-    if (unit >= n_units) return;
+    const uint32_t lin = xcd * per_xcd + idx;  // each XCD owns a contiguous range of the (unit, owner tile) order
+    if (lin >= total) return;
+    const uint32_t unit = lin / o_tiles, ot = lin - unit * o_tiles;  // unit = (subsequence or batch element) * heads + head
     const uint32_t bb = unit / (uint32_t)a.heads, head = unit - bb * (uint32_t)a.heads;
     uint32_t p = 0, q = 0, b0 = bb;
     if (a.g.mode != MODE_DENSE) {
@@ -281,9 +281,10 @@ static hipError_t launch_mode(const BwdArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
     const uint32_t o_tiles = ((uint32_t)a.g.n_sub + 32u * BNW - 1u) / (32u * BNW);
-    const uint64_t blocks = (uint64_t)((n_units + 7u) / 8u * 8u) * o_tiles;
-    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    attn_bwd_kernel<D, MODE><<<(uint32_t)blocks, BNT, 0, stream>>>(a, o_tiles, n_units);
+    const uint64_t total = (uint64_t)n_units * o_tiles;
+    if (total > 0x7ffffff0ull) return hipErrorInvalidConfiguration;
+    const uint32_t per_xcd = (uint32_t)((total + 7u) / 8u);
+    attn_bwd_kernel<D, MODE><<<8u * per_xcd, BNT, 0, stream>>>(a, o_tiles, (uint32_t)total, per_xcd);
     return hipGetLastError();
 }
 

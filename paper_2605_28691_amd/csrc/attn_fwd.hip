@@ -36,8 +36,9 @@
 //     the original layout and no permuted copy exists.  A thread stages part of one row per tile and advances its
 //     (row, column) position by 64 keys with adds and one wrap, so the index arithmetic is a handful of full-rate
 //     24-bit multiply-adds per thread per 64 keys.
-//   * Workgroups are numbered so that all query tiles of one unit run on the same XCD (workgroup id mod 8 selects
-//     the XCD under round-robin dispatch) and walk K/V in step: the per-XCD L2 then serves the re-reads.
+//   * Workgroups are numbered so that the query tiles of one unit run on the same XCD (workgroup id mod 8 selects
+//     the XCD under round-robin dispatch; every XCD owns a contiguous eighth of the (unit, tile) order) and walk K/V in
+//     step: the per-XCD L2 then serves the re-reads.
 #include <type_traits>
 
 #include "kernels.h"
@@ -122,7 +123,7 @@ __device__ inline size_t scattered_row(const AttnArgs& a, uint32_t sb, uint32_t 
 }
 
 template <int D, int QT, bool GROUP, bool PAD>
-__global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
+__global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t total, uint32_t per_xcd) {
     using TL = Tile<D>;
     constexpr int KS = D / 16;     // MFMA steps along head_dim for S^T = K Q^T
     constexpr int MT = D / 32;     // 32-row blocks of O^T
@@ -135,11 +136,12 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t lq = lane & 31u, h = lane >> 5;
 
-    // workgroup -> (unit, query tile): id%8 is the XCD, each XCD owns units xcd, xcd+8, ...
+    // workgroup -> (unit, query tile): id%8 is the XCD; each XCD owns a contiguous range of the (unit, tile) order, so that the
+    // tiles of a unit run on one XCD (two at a range boundary) and the load is even for any number of units
     const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
-    const uint32_t ul = idx / q_tiles, qt = idx - ul * q_tiles;
-    const uint32_t unit = ul * 8u + xcd;
-    if (unit >= n_units) return;
+    const uint32_t lin = xcd * per_xcd + idx;
+    if (lin >= total) return;
+    const uint32_t unit = lin / q_tiles, qt = lin - unit * q_tiles;
     const uint32_t bb = unit / (uint32_t)a.heads, head = unit - bb * (uint32_t)a.heads;
     uint32_t p = 0, q = 0, b0 = bb;
     if (a.g.mode != MODE_DENSE) {
@@ -578,10 +580,10 @@ static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
     const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 32u * NW * QT - 1u) / (32u * NW * QT);
-    const uint32_t units_padded = (n_units + 7u) / 8u * 8u;
-    const uint64_t blocks = (uint64_t)units_padded * q_tiles;
-    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    attn_fwd_bf16_kernel<D, QT, GROUP, PAD><<<(uint32_t)blocks, NTHREADS, 0, stream>>>(a, q_tiles, n_units);
+    const uint64_t total = (uint64_t)n_units * q_tiles;
+    if (total > 0x7ffffff0ull) return hipErrorInvalidConfiguration;
+    const uint32_t per_xcd = (uint32_t)((total + 7u) / 8u);
+    attn_fwd_bf16_kernel<D, QT, GROUP, PAD><<<8u * per_xcd, NTHREADS, 0, stream>>>(a, q_tiles, (uint32_t)total, per_xcd);
     return hipGetLastError();
 }
 

@@ -45,7 +45,7 @@ __device__ inline void lane_pair_f(float x, float& lo, float& hi) {
 
 template <int D>
 __attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD8, WAVES_PER_SIMD8)))
-__global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t n_units) {
+__global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t total, uint32_t per_xcd) {
     constexpr int NJ = D / 64;         // 64-channel MFMA steps of S^T = K Q^T
     constexpr int MT = D / 32;         // 32-channel blocks of O^T
     constexpr int K_STRIDE = D + 16;   // bytes
@@ -63,9 +63,9 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t lq = lane & 31u, h = lane >> 5;
     const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
-    const uint32_t ul = idx / q_tiles, qt = idx - ul * q_tiles;
-    const uint32_t unit = ul * 8u + xcd;  // unit = sb * heads + head
-    if (unit >= n_units) return;
+    const uint32_t lin = xcd * per_xcd + idx;  // each XCD owns a contiguous range of the (unit, tile) order
+    if (lin >= total) return;
+    const uint32_t unit = lin / q_tiles, qt = lin - unit * q_tiles;  // unit = sb * heads + head
     const uint32_t sb = unit / (uint32_t)a.heads, head = unit - sb * (uint32_t)a.heads;
     const uint32_t n_seq = (uint32_t)a.g.n_sub, n_blk = a.n_blk;
     const size_t C = (size_t)a.heads * D;  // bytes per position in the sparse layout
@@ -279,9 +279,10 @@ static hipError_t launch_fp8_t(const Fp8AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
     const uint32_t q_tiles = ((uint32_t)a.g.n_sub + 32u * NW8 - 1u) / (32u * NW8);
-    const uint64_t blocks = (uint64_t)((n_units + 7u) / 8u * 8u) * q_tiles;
-    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    attn_fwd_fp8_kernel<D><<<(uint32_t)blocks, NT8, 0, stream>>>(a, q_tiles, n_units);
+    const uint64_t total = (uint64_t)n_units * q_tiles;
+    if (total > 0x7ffffff0ull) return hipErrorInvalidConfiguration;
+    const uint32_t per_xcd = (uint32_t)((total + 7u) / 8u);
+    attn_fwd_fp8_kernel<D><<<8u * per_xcd, NT8, 0, stream>>>(a, q_tiles, (uint32_t)total, per_xcd);
     return hipGetLastError();
 }
 
