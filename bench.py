@@ -259,6 +259,12 @@ def main() -> int:
         extras["pad720p_token_ms"] = round(pad_ms, 4)
         extras["pad720p_real_tflops"] = round(real_flops / pad_ms / 1e9, 2)
         del qp, kp, vp, op
+    if "dense_ms" in extras and "fused_group_ms" in extras:
+        # the paper's 40-block model (Sec. 4.1): 8 full-attention blocks and 32 sparse ones, token-wise and group-wise alternating;
+        # attention time of the stack from the per-call figures above, against 40 full-attention calls
+        hyb = 8 * extras["dense_ms"] + 16 * ms + 16 * extras["fused_group_ms"]
+        extras["hybrid_stack_attention_ms"] = round(hyb, 2)
+        extras["hybrid_stack_speedup_vs_all_dense"] = round(40 * extras["dense_ms"] / hyb, 3)
     if extras:
         result["extras"] = extras
 
