@@ -325,8 +325,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
             for (int e = 0; e < 8; e += 2) {
                 const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[g * 8 + e], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s[g * 8 + e + 1], c, -mc))};
                 const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
-                // the row sum is taken over the rounded probabilities, the same values the second product uses
-                lsum = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum, false);
+                lsum += pe[0] + pe[1];  // row sum over the fp32 probabilities (two plain adds measure faster than one bf16 dot2)
                 pk[e] = pb[0];
                 pk[e + 1] = pb[1];
             }
@@ -382,7 +381,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     };
     // Hand-ordered version of a full, unmasked step: the instruction order is fixed group by group with scheduling
     // fences, and the exponentials are taken against the reference the row already has, so the common path computes no
-    // maximum at all: per key only fma, exp, half a bf16 pack and half a dot2 (row sum).  The guard is the row sum itself:
+    // maximum at all: per key only fma, exp, half a bf16 pack and an add (row sum).  The guard is the row sum itself:
     // if a lane's 16 probabilities add up to 2^16 or more (always on the first block, where the reference is -inf), the
     // wavefront takes the rare path, which finds the true maximum, redoes the block's exponentials against it and rescales
     // O and l.  Probabilities up to 2^16 are harmless: bf16 keeps their relative precision and O, l are fp32.
@@ -440,7 +439,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
                 for (int e = 2 * (g * 8 / NG); e < 2 * ((g + 1) * 8 / NG); e += 2) {
                     const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, -mc[qi])), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, -mc[qi]))};
                     const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
-                    lsum[qi] = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum[qi], false);
+                    lsum[qi] += pe[0] + pe[1];
                     pk[qi][e / 8][e % 8] = pb[0];
                     pk[qi][e / 8][e % 8 + 1] = pb[1];
                 }
