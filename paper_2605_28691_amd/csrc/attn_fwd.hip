@@ -7,7 +7,7 @@
 // Mapping onto the hardware
 //   * One workgroup = 8 wavefronts (two per SIMD), each owning 32 query rows for the whole key walk: 256 queries share
 //     every K/V tile that is brought into LDS, which halves the L2 -> LDS traffic per MFMA compared with 128 queries.
-//     One workgroup per CU (<= 256 VGPRs per lane, 74 KiB LDS).
+//     One workgroup per CU (<= 256 VGPRs per lane, 64 KiB LDS).
 //   * The products are formed transposed, S^T = K Q^T and O^T = V^T P^T, with v_mfma_f32_32x32x16_bf16.  In the
 //     32x32 accumulator layout lane l holds column l%32, so every lane owns ONE query: its 16 registers per 32-key
 //     block are 16 keys of that query, and the exponentiated accumulator registers, rounded to bf16, ARE the B operand
@@ -26,11 +26,13 @@
 //     the true maximum, redoes the block against it and rescales l; O is rescaled at the start of the next step in a
 //     block that holds only the in-place multiplies.  Numerator and denominator always use the same reference, so the
 //     result is exact up to rounding; probabilities up to 2^16 keep their relative precision in bf16, O and l are fp32.
-//   * K and V tiles of 64 keys are staged global -> registers -> LDS, double buffered, K one tile ahead of V (a
-//     window of two steps reads K tile W and V tile W-1), one barrier per window; the global loads of a tile are issued
-//     a whole window before their LDS stores.  K is read back as the A operand with 16-byte reads (rows padded to
-//     D*2+16 bytes); V^T is read with ds_read_b64_tr_b16, the gfx950 transposing LDS read (rows padded to D*2+64
-//     bytes), so V stays row-major in LDS.
+//   * K and V tiles of 64 keys go from global memory straight into LDS (global_load_lds_dwordx4, no staging registers,
+//     no LDS store instructions), double buffered, K one tile ahead of V (a window of two steps reads K tile W and V tile
+//     W-1), one barrier per window; the loads of a tile are enqueued a whole window before they are waited for.  LDS rows
+//     are packed (a direct load writes 64 consecutive 16-byte chunks) and bank conflicts are avoided by an XOR swizzle of
+//     the chunk position with the row number, chosen so that both the 16-byte fragment reads of K (16 consecutive rows)
+//     and the transposing reads of V^T (ds_read_b64_tr_b16, 4 consecutive rows of 64 bytes) touch every bank once; V
+//     stays row-major in LDS.  (Three buffers with a two-window lead and a fence-free barrier measured slower.)
 //   * Row addresses come from the Skiparse index map: in the dense mode position j is row j, in the sparse modes it is
 //     the token the rearrangement (Algorithm 1) would have put at position j, so q, k, v are read and out is written in
 //     the original layout and no permuted copy exists.  A thread stages part of one row per tile and advances its
@@ -64,12 +66,16 @@ constexpr float RESCALE_LOG2 = 8.0f;  // the reference maximum is only raised wh
 template <int D>
 struct Tile {
     static constexpr int CH = D / 8;                     // 16-byte chunks per row
-    static constexpr int TPR = NTHREADS / KT;            // threads that stage one row of a 64-key tile
-    static constexpr int CPT = CH / TPR;                 // 16-byte chunks per thread
-    static constexpr int K_STRIDE = D * 2 + 16;          // bytes; +16 spreads the 16-byte reads of 16 rows over all banks
-    static constexpr int V_STRIDE = D * 2 + 64;          // bytes; +64 keeps the 4 rows of a transposing read on distinct banks
-    static constexpr int K_BYTES = KT * K_STRIDE;
-    static constexpr int V_BYTES = KT * V_STRIDE;
+    static constexpr int RB = D * 2;                     // row bytes in LDS: rows are packed, bank conflicts are avoided by a swizzle
+    static constexpr int RPI = 64 / CH;                  // rows covered by one direct-to-LDS instruction of a wavefront (64 chunks)
+    static constexpr int IPW = CH / NW;                  // such instructions per wavefront and 64-row tile
+    static constexpr int TILE_BYTES = KT * RB;
+    static_assert(IPW >= 1 && IPW * NW == CH, "a tile is CH instructions, spread evenly over the wavefronts");
+    // Chunk c of row r is stored at chunk position c ^ swz(r).  The 16-byte fragment reads of 16 consecutive rows and the
+    // transposing reads of 4 consecutive rows (64 bytes each) then both touch every bank once.
+    __host__ __device__ static constexpr uint32_t swz(uint32_t r) {
+        return D == 128 ? (((r & 3u) << 2) | ((r >> 2) & 3u)) : ((((r >> 1) & 1u) << 2) | ((r >> 2) & 3u));
+    }
 };
 
 // Exchange between lanes l and l^32 (the two halves of one query's keys) with v_permlane32_swap: afterwards `lo` is
@@ -128,12 +134,14 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     constexpr int KS = D / 16;     // MFMA steps along head_dim for S^T = K Q^T
     constexpr int MT = D / 32;     // 32-row blocks of O^T
     constexpr int BR = 32 * NW * QT;   // query rows per workgroup: QT tiles of 32 per wavefront
-    __shared__ __attribute__((aligned(16))) char lds[2 * TL::K_BYTES + 2 * TL::V_BYTES];
+    // four separate arrays: the compiler must be able to tell that the tile being filled is not the tile being read
+    __shared__ __attribute__((aligned(1024))) char kbuf0[TL::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char kbuf1[TL::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char vbuf0[TL::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char vbuf1[TL::TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char kmask[4][KT];  // PAD only: 1 = real key, per row of the last 4 K tiles
-    char* const lds_k = lds;
-    char* const lds_v = lds + 2 * TL::K_BYTES;
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uniform(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
 
     // workgroup -> (unit, query tile): id%8 is the XCD; each XCD owns a contiguous range of the (unit, tile) order, so that the
@@ -178,69 +186,85 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         for (int ks = 0; ks < KS; ks++) qf[qi][ks] = *(const bf16x8*)(Qg + q_row_off[qi] + ks * 16 + 8 * h);
     }
 
-    // ---- staging: TPR threads per row of a 64-key tile.  K chunks of a thread are contiguous (st_piece*CPT + i), V chunks
-    // are interleaved (st_piece + TPR*i).
-    const uint32_t st_row = tid / TL::TPR, st_piece = tid % TL::TPR;
-    u32x4 kreg[TL::CPT], vreg[TL::CPT];  // staging registers: loaded during one window, stored to LDS at the start of the next
-    // Byte offset of this thread's row of a tile, relative to the unit's base (fits 32 bits: checked on the host).
-    // Tiles are visited in order, so (r, ws) = (j / Ws, j % Ws) of the row are advanced by 64 positions with adds and one
-    // wrap instead of being divided out again; the products use 24-bit multiplies (operands checked on the host).
+    // ---- staging: K/V tiles of 64 rows go from global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes
+    // land at the instruction's LDS base + 16*l, so one instruction of a wavefront fills RPI whole rows).  A wavefront issues IPW
+    // such instructions per tile; lane l fetches, for row l/CH of the instruction's rows, the chunk that the swizzle puts at
+    // position l%CH.  The row addresses come from the index map.
+    // Byte offset of a row relative to the unit's base (fits 32 bits: checked on the host).  Tiles are visited in order, so
+    // (r, ws) = (j / Ws, j % Ws) of a lane's rows are advanced by 64 positions with adds and one wrap instead of being divided out
+    // again; the products use 24-bit multiplies (operands checked on the host).
     const uint32_t Ws = a.g.ws.d, row_bytes = (uint32_t)C * 2u;
     const uint32_t last_off = PAD ? 0u : src_token(a.g, p, q, n_seq - 1u) * row_bytes;  // rows past the end read the last valid row
-    bool cur_valid = true, kreg_valid = true;  // PAD: whether the row whose offset was formed last / the row held in kreg is a real token
-    uint32_t st_r = a.g.ws.div(st_row), st_ws = st_row - st_r * Ws;  // position of tile 0's row (st_row < 64 <= any range limit)
-    uint32_t st_j = st_row;
     const uint32_t row_c = p * a.g.cmul, col_c = q * a.g.cmul;
-    auto row_off_now = [&]() -> uint32_t {
+    uint32_t st_row[TL::IPW], st_r[TL::IPW], st_ws[TL::IPW], st_j[TL::IPW], st_cb[TL::IPW];
+    bool st_valid[TL::IPW];  // PAD: whether the row whose offset was formed last is a real token
+#pragma unroll
+    for (int i = 0; i < TL::IPW; i++) {
+        st_row[i] = (wave * TL::IPW + i) * TL::RPI + lane / TL::CH;  // row of the tile (< 64 <= any range limit)
+        st_j[i] = st_row[i];
+        st_r[i] = a.g.ws.div(st_row[i]);
+        st_ws[i] = st_row[i] - st_r[i] * Ws;
+        st_cb[i] = ((lane % TL::CH) ^ TL::swz(st_row[i])) * 16u;  // byte offset, inside the row, of the chunk this lane fetches
+        st_valid[i] = true;
+    }
+    auto row_off_now = [&](int i) __attribute__((always_inline)) -> uint32_t {
         if (PAD) {  // positions are divided out again: the padded variant is not the fast path
             bool real;
-            const uint32_t tok = src_token_padded(a.g, p, q, st_j < n_seq ? st_j : 0u, &real);
-            cur_valid = real && st_j < n_seq;
-            return cur_valid ? tok * row_bytes : 0u;  // padding rows read token 0; their logits are masked
+            const uint32_t tok = src_token_padded(a.g, p, q, st_j[i] < n_seq ? st_j[i] : 0u, &real);
+            st_valid[i] = real && st_j[i] < n_seq;
+            return st_valid[i] ? tok * row_bytes : 0u;  // padding rows read token 0; their logits are masked
         }
-        uint32_t row = mad24(st_r, a.g.a, row_c);
-        uint32_t w = mad24(st_ws, a.g.a, col_c);
+        uint32_t row = mad24(st_r[i], a.g.a, row_c);
+        uint32_t w = mad24(st_ws[i], a.g.a, col_c);
         if (GROUP) {
-            row = mad24(a.g.sdiv.div(st_r), a.g.b, row);
-            w = mad24(a.g.sdiv.div(st_ws), a.g.b, w);
+            row = mad24(a.g.sdiv.div(st_r[i]), a.g.b, row);
+            w = mad24(a.g.sdiv.div(st_ws[i]), a.g.b, w);
         }
         const uint32_t off = mad24(mad24(row, (uint32_t)a.g.W, w), row_bytes, 0u);
-        return st_j < n_seq ? off : last_off;
+        return st_j[i] < n_seq ? off : last_off;
     };
-    auto advance_tile = [&]() {
-        st_j += KT;
-        st_r += a.g.step_r;
-        st_ws += a.g.step_w;
-        const bool wrap = st_ws >= Ws;
-        st_ws = wrap ? st_ws - Ws : st_ws;
-        st_r = wrap ? st_r + 1u : st_r;
+    struct RowOffs {
+        uint32_t off[TL::IPW];
+        bool valid[TL::IPW];
     };
-    auto tile_row_off_next = [&]() -> uint32_t {  // offset of the next tile's row; call once per tile, in order
-        advance_tile();
-        return row_off_now();
-    };
-    auto load_k = [&](uint32_t off) {
-        kreg_valid = cur_valid;
+    auto offs_now = [&]() __attribute__((always_inline)) -> RowOffs {
+        RowOffs o;
 #pragma unroll
-        for (int i = 0; i < TL::CPT; i++)
-            kreg[i] = *(const u32x4*)((const char*)Kg + off + (st_piece * TL::CPT + i) * 16);
+        for (int i = 0; i < TL::IPW; i++) {
+            o.off[i] = row_off_now(i);
+            o.valid[i] = st_valid[i];
+        }
+        return o;
     };
-    auto load_v = [&](uint32_t off) {
+    auto offs_next = [&]() __attribute__((always_inline)) -> RowOffs {  // offsets of the next tile's rows; call once per tile, in order
 #pragma unroll
-        for (int i = 0; i < TL::CPT; i++) vreg[i] = *(const u32x4*)((const char*)Vg + off + (st_piece + TL::TPR * i) * 16);
+        for (int i = 0; i < TL::IPW; i++) {
+            st_j[i] += KT;
+            st_r[i] += a.g.step_r;
+            st_ws[i] += a.g.step_w;
+            const bool wrap = st_ws[i] >= Ws;
+            st_ws[i] = wrap ? st_ws[i] - Ws : st_ws[i];
+            st_r[i] = wrap ? st_r[i] + 1u : st_r[i];
+        }
+        return offs_now();
     };
-    auto store_k = [&](uint32_t tile) {
-        const uint32_t buf = tile & 1u;
-        if (PAD && st_piece == 0) kmask[tile & 3u][st_row] = kreg_valid ? 1 : 0;
+    // enqueue the loads of one tile; they are complete (visible in LDS after the next barrier) once tile_landed() has returned
+    auto issue_tile = [&](const __bf16* g, char* buf, const RowOffs& o) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < TL::CPT; i++)
-            *(u32x4*)(lds_k + buf * TL::K_BYTES + st_row * TL::K_STRIDE + (st_piece * TL::CPT + i) * 16) = kreg[i];
+        for (int i = 0; i < TL::IPW; i++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)g + o.off[i] + st_cb[i]),
+                                             (LDS_PTR(void))(buf + (wave * TL::IPW + i) * 1024u), 16, 0, 0);
     };
-    auto store_v = [&](uint32_t buf) {
+    auto issue_k = [&](uint32_t tile, char* buf, const RowOffs& o) __attribute__((always_inline)) {
+        if (PAD) {
 #pragma unroll
-        for (int i = 0; i < TL::CPT; i++)
-            *(u32x4*)(lds_v + buf * TL::V_BYTES + st_row * TL::V_STRIDE + (st_piece + TL::TPR * i) * 16) = vreg[i];
+            for (int i = 0; i < TL::IPW; i++)
+                if (lane % TL::CH == 0) kmask[tile & 3u][st_row[i]] = o.valid[i] ? 1 : 0;
+        }
+        issue_tile(Kg, buf, o);
     };
+    auto issue_v = [&](char* buf, const RowOffs& o) __attribute__((always_inline)) { issue_tile(Vg, buf, o); };
+    auto tile_landed = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     // ---- running state: every lane tracks its own query (lanes l and l^32 hold the same m_ref; l_run is a partial sum)
     f32x16 oacc[QT][MT];
@@ -263,7 +287,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     bool pending = false;  // wave-uniform
 #pragma unroll
     for (int qi = 0; qi < QT; qi++) alpha_pending[qi] = 1.f;
-    auto apply_pending = [&]() {
+    auto apply_pending = [&]() __attribute__((always_inline)) {
         if (__builtin_expect(pending, 0)) {
 #pragma unroll
             for (int qi = 0; qi < QT; qi++)
@@ -276,13 +300,23 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     };
 
     // LDS read offsets that do not depend on the tile
-    const uint32_t k_rd = lq * TL::K_STRIDE + h * 16;  // + half*32*K_STRIDE + ks*32
+    uint32_t k_rd[KS];  // K fragment of MFMA step ks: row lq (+ 32 for the second half), chunk 2*ks + h at its swizzled position
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) k_rd[ks] = lq * TL::RB + (((uint32_t)(2 * ks) + h) ^ TL::swz(lq)) * 16u;
     // transposing V read: a 16-lane group covers 4 keys x 16 channels; lane i of the group addresses key i/4, channels 4*(i%4)..
     const uint32_t li = lane & 15u, lgrp = (lane >> 4) & 1u;
-    const uint32_t v_rd = (4 * h + (li >> 2)) * TL::V_STRIDE + (lgrp * 16 + 4 * (li & 3u)) * 2;  // + (half*32 + m2*16 (+8))*V_STRIDE + mt*64
+    uint32_t v_rd[2][MT];  // [second 4-row group][channel block]: + (half*32 + m2*16)*RB
+#pragma unroll
+    for (int sec = 0; sec < 2; sec++)
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            const uint32_t row = 4 * h + (li >> 2) + 8 * sec;  // adding 16*m2 + 32*half does not change the swizzle (low 4 bits)
+            const uint32_t ch = (uint32_t)(mt * 4) + lgrp * 2 + ((li & 3u) >> 1);
+            v_rd[sec][mt] = row * TL::RB + ((ch ^ TL::swz(row)) * 16u) + 8 * (li & 1u);
+        }
 
     // S(block) = K(block) Q^T from K tile buffer kb, 32-key half `half`; each K fragment feeds all QT query tiles
-    auto qk = [&](const char* kb, int half, f32x16 (&s)[QT]) {
+    auto qk = [&](const char* kb, int half, f32x16 (&s)[QT]) __attribute__((always_inline)) {
         f32x16 acc[QT];
 #pragma unroll
         for (int qi = 0; qi < QT; qi++)
@@ -290,7 +324,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
             for (int r = 0; r < 16; r++) acc[qi][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
-            const bf16x8 kf = *(const bf16x8*)(kb + k_rd + half * 32 * TL::K_STRIDE + ks * 32);
+            const bf16x8 kf = *(const bf16x8*)(kb + k_rd[ks] + half * 32 * TL::RB);
 #pragma unroll
             for (int qi = 0; qi < QT; qi++) {
                 acc[qi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qi][ks], acc[qi], 0, 0, 0);
@@ -300,23 +334,23 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         for (int qi = 0; qi < QT; qi++) s[qi] = acc[qi];
     };
     // O^T += V(block)^T P(block)^T from V tile buffer vb, 32-key half `half`
-    auto pv = [&](const char* vb, int half, const bf16x8 (&pf)[QT][2]) {
+    auto pv = [&](const char* vb, int half, const bf16x8 (&pf)[QT][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int m2 = 0; m2 < 2; m2++)
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
-                const char* va = vb + v_rd + (half * 32 + m2 * 16) * TL::V_STRIDE + mt * 64;
-                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))va);
-                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + 8 * TL::V_STRIDE));
+                const char* va = vb + (half * 32 + m2 * 16) * TL::RB;
+                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[0][mt]));
+                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[1][mt]));
                 const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                 for (int qi = 0; qi < QT; qi++)
                     oacc[qi][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qi][m2], oacc[qi][mt], 0, 0, 0);
             }
     };
-    auto max3 = [](float x, float y, float z) { return fmaxf(fmaxf(x, y), z); };
+    auto max3 = [](float x, float y, float z) __attribute__((always_inline)) { return fmaxf(fmaxf(x, y), z); };
     // exponentials of one block against the reference mc (= m_ref * c): bf16 probabilities and their fp32 sum
-    auto exps = [&](const f32x16& s, float mc, bf16x8 (&pf)[2]) -> float {
+    auto exps = [&](const f32x16& s, float mc, bf16x8 (&pf)[2]) __attribute__((always_inline)) -> float {
         float lsum = 0.f;
 #pragma unroll
         for (int g = 0; g < 2; g++) {
@@ -337,7 +371,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     //   QK(b+1) -> sreg[PAR^1]   softmax(b): sreg[PAR] -> preg[PAR]   PV(b-1) with preg[PAR^1]
     // Generic form, used for the first and last windows (optional QK / PV, key masking); instruction order is left to
     // the compiler.  The steady-state windows use step_manual below.
-    auto step = [&](auto DO_QK, auto DO_PV, auto MASK, auto PARC, uint32_t blk, const char* kb, const char* vb) {
+    auto step = [&](auto DO_QK, auto DO_PV, auto MASK, auto PARC, uint32_t blk, const char* kb, const char* vb) __attribute__((always_inline)) {
         constexpr int PAR = decltype(PARC)::value;
         apply_pending();
         if (decltype(DO_QK)::value) qk(kb, PAR ^ 1, sreg[PAR ^ 1]);
@@ -386,21 +420,21 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     // wavefront takes the rare path, which finds the true maximum, redoes the block's exponentials against it and rescales
     // O and l.  Probabilities up to 2^16 are harmless: bf16 keeps their relative precision and O, l are fp32.
     // LDS fragments are read two MFMA groups ahead and every fragment feeds the MFMAs of all QT query tiles.
-    auto step_manual = [&](auto PARC, const char* kb, const char* vb) {
+    auto step_manual = [&](auto PARC, const char* kb, const char* vb) __attribute__((always_inline)) {
         constexpr int PAR = decltype(PARC)::value;
         constexpr int NPV = 2 * MT, NQK = KS, NG = NPV + NQK;
         // MFMA groups alternate between the two products (PV, QK, PV, QK, ...: NPV == NQK), so consecutive MFMAs never
         // depend on each other: group g is PV group g/2 when g is even and QK group g/2 when g is odd.
         static_assert(NPV == NQK, "the two products have the same number of MFMA groups");
-        auto read_frag = [&](int g) -> bf16x8 {
+        auto read_frag = [&](int g) __attribute__((always_inline)) -> bf16x8 {
             const int i = g / 2;
             if (g % 2 == 0) {  // fragment of PV group i: 16-key group m2 = i / MT, channel block mt = i % MT
-                const char* va = vb + v_rd + ((PAR ^ 1) * 32 + (i / MT) * 16) * TL::V_STRIDE + (i % MT) * 64;
-                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))va);
-                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + 8 * TL::V_STRIDE));
+                const char* va = vb + ((PAR ^ 1) * 32 + (i / MT) * 16) * TL::RB;
+                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[0][i % MT]));
+                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[1][i % MT]));
                 return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
-            return *(const bf16x8*)(kb + k_rd + (PAR ^ 1) * 32 * TL::K_STRIDE + i * 32);
+            return *(const bf16x8*)(kb + k_rd[i] + (PAR ^ 1) * 32 * TL::RB);
         };
         apply_pending();
         bf16x8 fr[NG];  // every fragment has its own name; lifetimes are short, so few registers are live at a time
@@ -481,63 +515,70 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
 
     const uint32_t n_tiles = (n_seq + KT - 1) / KT;
 
-    // Staging schedule.  Window W reads K tile W and V tile W-1 from LDS.  At its start it stores the registers that were
-    // loaded during window W-1 (K tile W+1 -> K buffer (W+1)&1, V tile W -> V buffer W&1; neither buffer is read in window
-    // W) and then issues the loads of K tile W+2 and V tile W+1, which have a whole window to arrive.
-    // ---- prologue: K tile 0 to LDS; K tile 1 and V tile 0 into registers
-    uint32_t off_k = row_off_now();  // tile 0
-    load_k(off_k);
-    load_v(off_k);
-    store_k(0);
-    uint32_t off_v = tile_row_off_next();  // tile 1 (clamped to the last row if it does not exist)
-    load_k(off_v);
+    // Staging schedule.  Window W reads K tile W and V tile W-1 from LDS.  At its start it enqueues the direct loads of K tile
+    // W+1 (into the K buffer that window W-1 read) and of V tile W (into the V buffer that window W-1 read); they have the whole
+    // window to land and are waited for just before the window's closing barrier.
+    // ---- prologue: K tile 0
+    RowOffs off_prev = offs_now();  // tile 0
+    issue_k(0, kbuf0, off_prev);
+    tile_landed();
     __syncthreads();
 
     // ---- window 0: QK(0), then step 0 without PV
     {
-        store_k(1);
-        store_v(0);
-        off_k = tile_row_off_next();  // tile 2
-        load_k(off_k);
-        load_v(off_v);                // tile 1
-        off_v = off_k;
-        qk(lds_k, 0, sreg[0]);
-        step(T_{}, F_{}, T_{}, P0{}, 0u, lds_k, lds_v);
+        const RowOffs off_new = offs_next();  // tile 1 (clamped to the last row if it does not exist)
+        issue_k(1, kbuf1, off_new);
+        issue_v(vbuf0, off_prev);
+        off_prev = off_new;
+        qk(kbuf0, 0, sreg[0]);
+        step(T_{}, F_{}, T_{}, P0{}, 0u, kbuf0, vbuf0);
+        tile_landed();
         __syncthreads();
     }
-    // ---- windows 1 .. n_tiles-2: all keys valid
-    uint32_t W = 1;
-    for (; W + 1 < n_tiles; W++) {
-        const char* kb = lds_k + (W & 1u) * TL::K_BYTES;
-        const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
-        store_k(W + 1u);              // K tile W+1
-        store_v(W & 1u);              // V tile W
-        off_k = tile_row_off_next();  // tile W+2
-        load_k(off_k);
-        load_v(off_v);                // tile W+1
-        off_v = off_k;
+    // ---- windows 1 .. n_tiles-2: all keys valid.  The parity of W selects the buffers at compile time.
+    auto window = [&](auto WP, uint32_t Wn) __attribute__((always_inline)) {
+        constexpr int WPAR = decltype(WP)::value;  // Wn & 1
+        char* const kb = WPAR ? kbuf1 : kbuf0;           // K tile Wn
+        char* const kb_fill = WPAR ? kbuf0 : kbuf1;      // K tile Wn+1
+        char* const vb = WPAR ? vbuf0 : vbuf1;           // V tile Wn-1
+        char* const vb_fill = WPAR ? vbuf1 : vbuf0;      // V tile Wn
+        const RowOffs off_new = offs_next();             // tile Wn+1
+        issue_k(Wn + 1u, kb_fill, off_new);
+        issue_v(vb_fill, off_prev);
+        off_prev = off_new;
         if (PAD) {  // every block takes the masked step
-            step(T_{}, T_{}, T_{}, P1{}, 2 * W - 1, kb, vb);
-            step(T_{}, T_{}, T_{}, P0{}, 2 * W, kb, vb);
+            step(T_{}, T_{}, T_{}, P1{}, 2 * Wn - 1, kb, vb);
+            step(T_{}, T_{}, T_{}, P0{}, 2 * Wn, kb, vb);
         } else {
             step_manual(P1{}, kb, vb);
             step_manual(P0{}, kb, vb);
         }
+        tile_landed();
         __syncthreads();
+    };
+    uint32_t W = 1;
+    for (; W + 2 < n_tiles; W += 2) {
+        window(P1{}, W);
+        window(P0{}, W + 1u);
+    }
+    if (W + 1 < n_tiles) {
+        window(P1{}, W);
+        W++;
     }
     // ---- window n_tiles-1 (if there is more than one tile): the last K tile, may hold keys past the end
     if (W < n_tiles) {
-        const char* kb = lds_k + (W & 1u) * TL::K_BYTES;
-        const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
-        store_v(W & 1u);  // V tile W, the last one
+        const char* kb = (W & 1u) ? kbuf1 : kbuf0;
+        const char* vb = (W & 1u) ? vbuf0 : vbuf1;
+        issue_v((W & 1u) ? vbuf1 : vbuf0, off_prev);  // V tile W, the last one
         step(T_{}, T_{}, T_{}, P1{}, 2 * W - 1, kb, vb);
         step(T_{}, T_{}, T_{}, P0{}, 2 * W, kb, vb);
+        tile_landed();
         __syncthreads();
         W++;
     }
     // ---- final window (W == n_tiles): softmax of the last block, the last two PVs
     {
-        const char* vb = lds_v + ((W + 1u) & 1u) * TL::V_BYTES;
+        const char* vb = (W & 1u) ? vbuf0 : vbuf1;  // V tile W-1
         step(F_{}, T_{}, T_{}, P1{}, 2 * W - 1, nullptr, vb);
         apply_pending();
         pv(vb, 1, preg[1]);
