@@ -543,16 +543,19 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         char* const vb = WPAR ? vbuf0 : vbuf1;           // V tile Wn-1
         char* const vb_fill = WPAR ? vbuf1 : vbuf0;      // V tile Wn
         const RowOffs off_new = offs_next();             // tile Wn+1
+        // K loads before the first step, V loads between the two steps: enqueueing all of them at once measured 1-3 % slower (the
+        // memory pipeline backs up), spreading them further over the MFMA groups slower still (each issue stalls the wavefront)
         issue_k(Wn + 1u, kb_fill, off_new);
-        issue_v(vb_fill, off_prev);
-        off_prev = off_new;
         if (PAD) {  // every block takes the masked step
             step(T_{}, T_{}, T_{}, P1{}, 2 * Wn - 1, kb, vb);
+            issue_v(vb_fill, off_prev);
             step(T_{}, T_{}, T_{}, P0{}, 2 * Wn, kb, vb);
         } else {
             step_manual(P1{}, kb, vb);
+            issue_v(vb_fill, off_prev);
             step_manual(P0{}, kb, vb);
         }
+        off_prev = off_new;
         tile_landed();
         __syncthreads();
     };
