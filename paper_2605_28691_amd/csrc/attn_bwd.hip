@@ -17,10 +17,12 @@
 // leave room for two wavefronts per SIMD; the price is that S is recomputed once more (8 matrix products instead of 7).
 //   * log-sum-exp and delta are per QUERY: per-lane constants in the dQ launch, per-streamed-row values (staged in LDS next
 //     to the tile, +inf / 0 past the end so that such rows contribute nothing) in the other two.
-//   * A streamed tile that is read both ways is kept twice in LDS, once with the row stride that suits 16-byte fragment
-//     reads (D*2+16 bytes) and once with the stride that suits ds_read_b64_tr_b16 (D*2+64 bytes).
+//   * Streamed tiles go from global memory straight into LDS (global_load_lds_dwordx4), rows packed, chunk positions XOR-swizzled
+//     with the row number so that a tile serves both the 16-byte fragment reads and ds_read_b64_tr_b16 without bank conflicts.
 //   * Rows are addressed through the Skiparse index map (Algorithm 1) exactly as in the forward kernel, so q, k, v, dO and the
 //     gradients are all in the original layout.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace skiparse {
@@ -45,19 +47,22 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     constexpr int KS = D / 16;   // MFMA steps along head_dim
     constexpr int MT = D / 32;   // 32-channel blocks of the gradient row
     constexpr int CH = D / 8;    // 16-byte chunks per row
-    constexpr int TPR = BNT / BT;        // threads staging one row
-    constexpr int CPT = CH / TPR;        // chunks per thread
-    constexpr int RS = D * 2 + 16;       // row stride for 16-byte fragment reads
-    constexpr int TS = D * 2 + 64;       // row stride for transposing reads
+    constexpr int RB = D * 2;    // row bytes in LDS (packed rows, swizzled chunk positions)
+    constexpr int RPI = 64 / CH; // rows filled by one direct-to-LDS instruction of a wavefront
+    constexpr int IPW = CH / BNW;  // such instructions per wavefront, tensor and tile
     constexpr bool TWO = MODE != BWD_DV; // second product M2 present
-    constexpr int R1_BYTES = BT * RS, T_BYTES = BT * TS, R2_BYTES = TWO ? BT * RS : 0;
-    constexpr int BUF_BYTES = R1_BYTES + T_BYTES + R2_BYTES;
-    static_assert(CPT >= 1 && CPT * TPR == CH, "staging split");
-    __shared__ __attribute__((aligned(16))) char lds[2 * BUF_BYTES];
+    constexpr int TILE_BYTES = BT * RB;
+    static_assert(IPW >= 1 && IPW * BNW == CH, "a tile is CH instructions, spread evenly over the wavefronts");
+    // two streamed tensors, double buffered; separate arrays so that the compiler can tell the tile being filled from the one
+    // being read
+    __shared__ __attribute__((aligned(1024))) char s1buf0[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char s1buf1[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char s2buf0[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char s2buf1[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) float row_l[2][BT];  // dK, dV: log2-domain log-sum-exp of the streamed queries
     __shared__ __attribute__((aligned(16))) float row_d[2][BT];  // dK: their delta
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
     const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
     const uint32_t lin = xcd * per_xcd + idx;  // each XCD owns a contiguous range of the (unit, owner tile) order
@@ -102,17 +107,29 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     }
     const float c = a.scale * LOG2E;  // exp(x*scale - L) = exp2(x*c - L*log2e)
 
-    // ---- staging of streamed tiles: TPR threads per row, CPT consecutive 16-byte chunks each
-    const uint32_t st_row = tid / TPR, st_piece = tid % TPR;
-    u32x4 r1[CPT], r2[CPT];
-    float rl = 0.f, rd = 0.f;
-    auto load_tile = [&](uint32_t t) __attribute__((always_inline)) {
-        const uint32_t j = t * BT + st_row;
-        const size_t off = (size_t)src_token(a.g, p, q, j < n_seq ? j : n_seq - 1u) * C * 2 + (st_piece * CPT) * 16;  // bytes
+    // ---- staging of streamed tiles: global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at the
+    // instruction's LDS base + 16*l, one instruction fills RPI rows).  Chunk c of row r is stored at chunk position c ^ swz(r),
+    // which keeps the 16-byte fragment reads (16 consecutive rows) and the transposing reads (4 consecutive rows of 64 bytes)
+    // both free of bank conflicts, so a tile that is read both ways is kept once.
+    auto swz = [](uint32_t r) __attribute__((always_inline)) -> uint32_t {
+        return D == 128 ? (((r & 3u) << 2) | ((r >> 2) & 3u)) : ((((r >> 1) & 1u) << 2) | ((r >> 2) & 3u));
+    };
+    uint32_t st_row[IPW], st_cb[IPW];
 #pragma unroll
-        for (int i = 0; i < CPT; i++) {
-            r1[i] = *(const u32x4*)(st1_g + off + i * 16);
-            r2[i] = *(const u32x4*)(st2_g + off + i * 16);
+    for (int i = 0; i < IPW; i++) {
+        st_row[i] = (wave * IPW + i) * RPI + lane / CH;
+        st_cb[i] = ((lane % CH) ^ swz(st_row[i])) * 16u;
+    }
+    float rl = 0.f, rd = 0.f;
+    auto issue_tile = [&](uint32_t t, char* b1, char* b2) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < IPW; i++) {
+            const uint32_t j = t * BT + st_row[i];
+            const size_t off = (size_t)src_token(a.g, p, q, j < n_seq ? j : n_seq - 1u) * C * 2 + st_cb[i];  // bytes
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st1_g + off),
+                                             (LDS_PTR(void))(b1 + (wave * IPW + i) * 1024u), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st2_g + off),
+                                             (LDS_PTR(void))(b2 + (wave * IPW + i) * 1024u), 16, 0, 0);
         }
         if (MODE != BWD_DQ && tid < BT) {  // per-query values of the streamed rows; rows past the end contribute nothing
             const uint32_t jj = t * BT + tid;
@@ -120,21 +137,13 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             rd = (MODE == BWD_DK && jj < n_seq) ? delta_u[jj] : 0.f;
         }
     };
-    auto store_tile = [&](uint32_t buf) __attribute__((always_inline)) {
-        char* base = lds + buf * BUF_BYTES;
-#pragma unroll
-        for (int i = 0; i < CPT; i++) {
-            const uint32_t ch = (st_piece * CPT + i) * 16;
-            *(u32x4*)(base + st_row * RS + ch) = r1[i];
-            if (MODE != BWD_DV) *(u32x4*)(base + R1_BYTES + st_row * TS + ch) = r1[i];  // A3 = first streamed tensor
-            if (MODE == BWD_DV) *(u32x4*)(base + R1_BYTES + st_row * TS + ch) = r2[i];  // A3 = dO
-            if (TWO) *(u32x4*)(base + R1_BYTES + T_BYTES + st_row * RS + ch) = r2[i];
-        }
+    auto store_rowvals = [&](uint32_t buf) __attribute__((always_inline)) {
         if (MODE != BWD_DQ && tid < BT) {
             row_l[buf][tid] = rl;
             row_d[buf][tid] = rd;
         }
     };
+    auto tile_landed = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     f32x16 acc[MT];
 #pragma unroll
@@ -142,19 +151,42 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[mt][r] = 0.f;
 
-    const uint32_t a_rd = lq * RS + h * 16;  // + blk*32*RS + ks*32
+    // fragment of MFMA step ks: row lq (+ 32*blk), chunk 2*ks + h at its swizzled position.  The position of step ks is that of
+    // step 0 with ks*32 XORed in (the row part lies above the chunk bits), so one register and an XOR per read can replace the
+    // table; the dK launch, the tightest on registers, does that.
+    constexpr bool ADDR_TABLE = MODE != BWD_DK;
+    const uint32_t a_rd0 = lq * RB + ((h ^ swz(lq)) * 16u);
+    uint32_t a_rd_tab[ADDR_TABLE ? KS : 1];
+    if (ADDR_TABLE) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) a_rd_tab[ks] = a_rd0 ^ (uint32_t)(ks * 32);
+    }
+    auto a_rd = [&](int ks) __attribute__((always_inline)) -> uint32_t { return ADDR_TABLE ? a_rd_tab[ks] : (a_rd0 ^ (uint32_t)(ks * 32)); };
     // transposing read: a 16-lane group covers 4 rows x 16 channels; lane i of the group addresses row i/4, channels 4*(i%4)..
     const uint32_t li = lane & 15u, lgrp = (lane >> 4) & 1u;
-    const uint32_t t_rd = (4 * h + (li >> 2)) * TS + (lgrp * 16 + 4 * (li & 3u)) * 2;  // + (blk*32 + m2*16 (+8))*TS + mt*64
+    uint32_t t_rd[2][MT];  // [second 4-row group][channel block]: + (blk*32 + g2*16)*RB
+#pragma unroll
+    for (int sec = 0; sec < 2; sec++)
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            const uint32_t row = 4 * h + (li >> 2) + 8 * sec;  // adding 16*g2 + 32*blk does not change the swizzle (low 4 bits)
+            const uint32_t ch = (uint32_t)(mt * 4) + lgrp * 2 + ((li & 3u) >> 1);
+            t_rd[sec][mt] = row * RB + ((ch ^ swz(row)) * 16u) + 8 * (li & 1u);
+        }
 
     const uint32_t n_t = (n_seq + BT - 1) / BT;
-    load_tile(0);
-    store_tile(0);
+    issue_tile(0, s1buf0, s2buf0);
+    store_rowvals(0);
+    tile_landed();
     __syncthreads();
-    for (uint32_t t = 0; t < n_t; t++) {
+    // one tile: enqueue the loads of the next tile into the other buffers, compute on this one, wait, barrier.  The parity of
+    // the tile (which buffers) is a compile-time constant.
+    auto do_tile = [&](auto PARC, uint32_t t) __attribute__((always_inline)) {
+        constexpr int PARITY = decltype(PARC)::value;  // t & 1
+        const char* t1 = PARITY ? s1buf1 : s1buf0;
+        const char* t2 = PARITY ? s2buf1 : s2buf0;
         const bool more = t + 1 < n_t;
-        if (more) load_tile(t + 1);
-        const char* base = lds + (t & 1u) * BUF_BYTES;
+        if (more) issue_tile(t + 1, PARITY ? s1buf0 : s1buf1, PARITY ? s2buf0 : s2buf1);
         const bool tail = MODE == BWD_DQ && !more && (n_seq % BT) != 0;  // dQ: streamed keys past the end are masked
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {
@@ -166,13 +198,13 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             }
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) {
-                const bf16x8 f1 = *(const bf16x8*)(base + a_rd + blk * 32 * RS + ks * 32);
+                const bf16x8 f1 = *(const bf16x8*)(t1 + a_rd(ks) + blk * 32 * RB);
                 m1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, own1[ks], m1, 0, 0, 0);
             }
             if (TWO) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++) {
-                    const bf16x8 f2 = *(const bf16x8*)(base + R1_BYTES + T_BYTES + a_rd + blk * 32 * RS + ks * 32);
+                    const bf16x8 f2 = *(const bf16x8*)(t2 + a_rd(ks) + blk * 32 * RB);
                     m2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, own2[ks], m2, 0, 0, 0);
                 }
             }
@@ -181,8 +213,8 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             if (MODE != BWD_DQ) {
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
-                    sl[g] = *(const f32x4*)&row_l[t & 1u][blk * 32 + 8 * g + 4 * h];
-                    if (MODE == BWD_DK) sd[g] = *(const f32x4*)&row_d[t & 1u][blk * 32 + 8 * g + 4 * h];
+                    sl[g] = *(const f32x4*)&row_l[PARITY][blk * 32 + 8 * g + 4 * h];
+                    if (MODE == BWD_DK) sd[g] = *(const f32x4*)&row_d[PARITY][blk * 32 + 8 * g + 4 * h];
                 }
             }
             bf16x8 rf[2];
@@ -214,16 +246,23 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             for (int g2 = 0; g2 < 2; g2++)
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++) {
-                    const char* ta = base + R1_BYTES + t_rd + (blk * 32 + g2 * 16) * TS + mt * 64;
-                    const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))ta);
-                    const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + 8 * TS));
+                    const char* ta = (MODE == BWD_DV ? t2 : t1) + (blk * 32 + g2 * 16) * RB;  // A3: dO for dV, else the first tensor
+                    const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[0][mt]));
+                    const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[1][mt]));
                     const bf16x8 tf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
                     acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, rf[g2], acc[mt], 0, 0, 0);
                 }
         }
-        if (more) store_tile((t + 1) & 1u);
+        if (more) store_rowvals(PARITY ^ 1);
+        tile_landed();
         __syncthreads();
+    };
+    uint32_t t = 0;
+    for (; t + 1 < n_t; t += 2) {
+        do_tile(std::integral_constant<int, 0>{}, t);
+        do_tile(std::integral_constant<int, 1>{}, t + 1u);
     }
+    if (t < n_t) do_tile(std::integral_constant<int, 0>{}, t);
 
     // ---- epilogue: lane owns row jo; register r of block mt is channel 32*mt + 8*(r/4) + 4*h + r%4
     if (own_valid) {
