@@ -152,18 +152,19 @@ def main() -> int:
     sections = set() if args.skip_extras else {x for x in args.extras.split(",") if x}
     extras = {}
     if "probe" in sections:
-        # what the matrix pipe sustains by itself on random operands (power-managed clock): nothing but MFMAs, 8 wavefronts per SIMD
+        # what the matrix pipe sustains by itself on random operands (power-managed clock): nothing but MFMAs, 2 wavefronts per
+        # SIMD (more wavefronts per SIMD measure lower: the pipe runs without gaps only on back-to-back MFMAs of one wavefront)
         gp = torch.Generator(device="cpu")
         gp.manual_seed(99)
         rnd = torch.randn(8192, generator=gp, dtype=torch.float32)
-        sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
-        for name, ops, fp8, n_it in (("bf16", rnd.to(torch.bfloat16).cuda(), False, 20000),
-                                     ("fp8", rnd.repeat(2).to(torch.float8_e4m3fn).view(torch.uint8).cuda(), True, 10000),
-                                     ("bf16_zero_operands", torch.zeros(8192, dtype=torch.bfloat16, device="cuda"), False, 20000)):
+        sink = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+        for name, ops, fp8, n_it in (("bf16", rnd.to(torch.bfloat16).cuda(), False, 80000),
+                                     ("fp8", rnd.repeat(2).to(torch.float8_e4m3fn).view(torch.uint8).cuda(), True, 40000),
+                                     ("bf16_zero_operands", torch.zeros(8192, dtype=torch.bfloat16, device="cuda"), False, 80000)):
             fl = [0.0]
 
             def probe():
-                fl[0] = sk.skiparse_mfma_probe(ops, sink, fp8, 2048, n_it)
+                fl[0] = sk.skiparse_mfma_probe(ops, sink, fp8, 512, n_it)
 
             p_ms = time_calls(probe, 5, 2)
             extras[f"mfma_only_{name}_tflops"] = round(fl[0] / p_ms / 1e9, 1)

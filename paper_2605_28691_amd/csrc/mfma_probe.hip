@@ -9,7 +9,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
-constexpr int PROBE_THREADS = 256;  // 4 wavefronts, one per SIMD; several workgroups share a compute unit
+constexpr int PROBE_THREADS = 256;  // 4 wavefronts, one per SIMD; 512 workgroups put two wavefronts on every SIMD of 256 compute units
 constexpr int PROBE_FRAGS = 4;      // operand pairs cycled through, so that consecutive MFMAs see different data
 
 // operands: at least PROBE_FRAGS * 2 * 64 * 32 bytes of arbitrary (e.g. random bf16 / e4m3) data
