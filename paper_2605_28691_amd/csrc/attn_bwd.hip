@@ -24,6 +24,7 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "lds_layout.h"
 
 namespace skiparse {
 
@@ -111,9 +112,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     // instruction's LDS base + 16*l, one instruction fills RPI rows).  Chunk c of row r is stored at chunk position c ^ swz(r),
     // which keeps the 16-byte fragment reads (16 consecutive rows) and the transposing reads (4 consecutive rows of 64 bytes)
     // both free of bank conflicts, so a tile that is read both ways is kept once.
-    auto swz = [](uint32_t r) __attribute__((always_inline)) -> uint32_t {
-        return D == 128 ? (((r & 3u) << 2) | ((r >> 2) & 3u)) : ((((r >> 1) & 1u) << 2) | ((r >> 2) & 3u));
-    };
+    auto swz = [](uint32_t r) __attribute__((always_inline)) -> uint32_t { return lds_swizzle<D>(r); };
     uint32_t st_row[IPW], st_cb[IPW];
 #pragma unroll
     for (int i = 0; i < IPW; i++) {

@@ -44,6 +44,7 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "lds_layout.h"
 
 namespace skiparse {
 
@@ -71,11 +72,8 @@ struct Tile {
     static constexpr int IPW = CH / NW;                  // such instructions per wavefront and 64-row tile
     static constexpr int TILE_BYTES = KT * RB;
     static_assert(IPW >= 1 && IPW * NW == CH, "a tile is CH instructions, spread evenly over the wavefronts");
-    // Chunk c of row r is stored at chunk position c ^ swz(r).  The 16-byte fragment reads of 16 consecutive rows and the
-    // transposing reads of 4 consecutive rows (64 bytes each) then both touch every bank once.
-    __host__ __device__ static constexpr uint32_t swz(uint32_t r) {
-        return D == 128 ? (((r & 3u) << 2) | ((r >> 2) & 3u)) : ((((r >> 1) & 1u) << 2) | ((r >> 2) & 3u));
-    }
+    // chunk c of row r is stored at chunk position c ^ swz(r): see lds_layout.h
+    __host__ __device__ static constexpr uint32_t swz(uint32_t r) { return lds_swizzle<D>(r); }
 };
 
 // Exchange between lanes l and l^32 (the two halves of one query's keys) with v_permlane32_swap: afterwards `lo` is
