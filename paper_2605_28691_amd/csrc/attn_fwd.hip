@@ -52,6 +52,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
@@ -101,7 +102,7 @@ __device__ inline size_t uniform(size_t x) {
 
 // GROUP selects the group-wise index map (two extra divisions by s per staged row); token-wise and dense use GROUP = false.
 // PAD selects the any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s, padding positions
-// are masked as keys (a validity byte per staged row in LDS) and skipped as queries; every block takes the masked step.
+// are masked as keys (a validity byte and a 0 / -inf logit bias per staged row in LDS) and skipped as queries.
 // Row of `out` for position j of subsequence sb of the input's sparse layout: the token's row in the original layout, or its
 // row in the sparse layout of the other pattern (Alg. 1: tsa_to_orig / gsa_to_orig, tsa_to_gsa / gsa_to_tsa).
 __device__ inline size_t scattered_row(const AttnArgs& a, uint32_t sb, uint32_t j) {
@@ -138,6 +139,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     __shared__ __attribute__((aligned(1024))) char vbuf0[TL::TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char vbuf1[TL::TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char kmask[4][KT];  // PAD only: 1 = real key, per row of the last 4 K tiles
+    __shared__ __attribute__((aligned(16))) float kbias[4][KT];          // PAD only: the same as a logit bias, 0 or -inf
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uniform(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
@@ -206,17 +208,17 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         st_valid[i] = true;
     }
     auto row_off_now = [&](int i) __attribute__((always_inline)) -> uint32_t {
-        if (PAD) {  // positions are divided out again: the padded variant is not the fast path
-            bool real;
-            const uint32_t tok = src_token_padded(a.g, p, q, st_j[i] < n_seq ? st_j[i] : 0u, &real);
-            st_valid[i] = real && st_j[i] < n_seq;
-            return st_valid[i] ? tok * row_bytes : 0u;  // padding rows read token 0; their logits are masked
-        }
         uint32_t row = mad24(st_r[i], a.g.a, row_c);
         uint32_t w = mad24(st_ws[i], a.g.a, col_c);
         if (GROUP) {
             row = mad24(a.g.sdiv.div(st_r[i]), a.g.b, row);
             w = mad24(a.g.sdiv.div(st_ws[i]), a.g.b, w);
+        }
+        if (PAD) {  // (row, w) are coordinates on the padded grid: row = t * H_pad + h
+            const uint32_t t = a.g.hpad.div(row), hh = row - t * a.g.hpad.d;
+            st_valid[i] = st_j[i] < n_seq && hh < (uint32_t)a.g.H_real && w < (uint32_t)a.g.W;
+            const uint32_t tok = mad24(mad24(t, (uint32_t)a.g.H_real, hh), (uint32_t)a.g.W, w);
+            return st_valid[i] ? mad24(tok, row_bytes, 0u) : 0u;  // padding rows read token 0; their logits are masked
         }
         const uint32_t off = mad24(mad24(row, (uint32_t)a.g.W, w), row_bytes, 0u);
         return st_j[i] < n_seq ? off : last_off;
@@ -257,7 +259,10 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         if (PAD) {
 #pragma unroll
             for (int i = 0; i < TL::IPW; i++)
-                if (lane % TL::CH == 0) kmask[tile & 3u][st_row[i]] = o.valid[i] ? 1 : 0;
+                if (lane % TL::CH == 0) {
+                    kmask[tile & 3u][st_row[i]] = o.valid[i] ? 1 : 0;
+                    kbias[tile & 3u][st_row[i]] = o.valid[i] ? 0.f : -INFINITY;
+                }
         }
         issue_tile(Kg, buf, o);
     };
@@ -418,7 +423,9 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     // wavefront takes the rare path, which finds the true maximum, redoes the block's exponentials against it and rescales
     // O and l.  Probabilities up to 2^16 are harmless: bf16 keeps their relative precision and O, l are fp32.
     // LDS fragments are read two MFMA groups ahead and every fragment feeds the MFMAs of all QT query tiles.
-    auto step_manual = [&](auto PARC, const char* kb, const char* vb) __attribute__((always_inline)) {
+    // In the any-resolution mode (PAD) the same step adds a per-key bias (0 for a real key, -inf for a padding position, staged
+    // next to the K tile) to the exponent, which costs one subtraction per key; `blk` is the block whose softmax this step does.
+    auto step_manual = [&](auto PARC, const char* kb, const char* vb, uint32_t blk) __attribute__((always_inline)) {
         constexpr int PAR = decltype(PARC)::value;
         constexpr int NPV = 2 * MT, NQK = KS, NG = NPV + NQK;
         // MFMA groups alternate between the two products (PV, QK, PV, QK, ...: NPV == NQK), so consecutive MFMAs never
@@ -447,6 +454,11 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
             lsum[qi] = 0.f;
             mc[qi] = m_ref[qi] * c;
         }
+        f32x4 bias[4];  // PAD: register r of the block is key 8*(r/4) + 4*h + r%4
+        if (PAD) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) bias[i] = *(const f32x4*)&kbias[(blk >> 1) & 3u][(blk & 1u) * 32u + 8 * i + 4 * h];
+        }
 #pragma unroll
         for (int g = 0; g < NG; g++) {
             if (g + LDS_AHEAD < NG) fr[g + LDS_AHEAD] = read_frag(g + LDS_AHEAD);
@@ -469,7 +481,9 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
                 const f32x16& s = sreg[PAR][qi];
 #pragma unroll
                 for (int e = 2 * (g * 8 / NG); e < 2 * ((g + 1) * 8 / NG); e += 2) {
-                    const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, -mc[qi])), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, -mc[qi]))};
+                    const float a0 = PAD ? bias[e >> 2][e & 3] - mc[qi] : -mc[qi];
+                    const float a1 = PAD ? bias[(e + 1) >> 2][(e + 1) & 3] - mc[qi] : -mc[qi];
+                    const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, a0)), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, a1))};
                     const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
                     lsum[qi] += pe[0] + pe[1];
                     pk[qi][e / 8][e % 8] = pb[0];
@@ -490,15 +504,20 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         if (__builtin_expect(redo != 0, 0)) {
 #pragma unroll
             for (int qi = 0; qi < QT; qi++) {
-                const f32x16& s = sreg[PAR][qi];
+                f32x16& s = sreg[PAR][qi];
+                if (PAD) {  // padding keys out of the way before the maximum is taken
+#pragma unroll
+                    for (int r = 0; r < 16; r++) s[r] += bias[r >> 2][r & 3];
+                }
                 const float mx = fmaxf(max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8])),
                                        max3(max3(s[9], s[10], s[11]), max3(s[12], s[13], s[14]), s[15]));
                 float lo, hi;
                 lane_pair(mx, lo, hi);
                 const float m_new = max3(m_ref[qi], lo, hi);
-                alpha_pending[qi] = __builtin_amdgcn_exp2f((m_ref[qi] - m_new) * c);  // 0 on the first block
+                // while no real key has been seen (a block of nothing but padding) the reference stays -inf: factor 1, exponent 0
+                alpha_pending[qi] = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f((m_ref[qi] - m_new) * c);  // 0 on the first real block
                 m_ref[qi] = m_new;
-                l_run[qi] = fmaf(l_run[qi], alpha_pending[qi], exps(s, m_new * c, preg[PAR][qi]));
+                l_run[qi] = fmaf(l_run[qi], alpha_pending[qi], exps(s, m_new == -INFINITY ? 0.f : m_new * c, preg[PAR][qi]));
             }
             pending = true;
         } else {
@@ -544,15 +563,9 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         // K loads before the first step, V loads between the two steps: enqueueing all of them at once measured 1-3 % slower (the
         // memory pipeline backs up), spreading them further over the MFMA groups slower still (each issue stalls the wavefront)
         issue_k(Wn + 1u, kb_fill, off_new);
-        if (PAD) {  // every block takes the masked step
-            step(T_{}, T_{}, T_{}, P1{}, 2 * Wn - 1, kb, vb);
-            issue_v(vb_fill, off_prev);
-            step(T_{}, T_{}, T_{}, P0{}, 2 * Wn, kb, vb);
-        } else {
-            step_manual(P1{}, kb, vb);
-            issue_v(vb_fill, off_prev);
-            step_manual(P0{}, kb, vb);
-        }
+        step_manual(P1{}, kb, vb, 2 * Wn - 1);
+        issue_v(vb_fill, off_prev);
+        step_manual(P0{}, kb, vb, 2 * Wn);
         off_prev = off_new;
         tile_landed();
         __syncthreads();
