@@ -169,6 +169,16 @@ def main() -> int:
             p_ms = time_calls(probe, 5, 2)
             extras[f"mfma_only_{name}_tflops"] = round(fl[0] / p_ms / 1e9, 1)
         result["roofline"]["attainable_mfma_only"] = extras["mfma_only_bf16_tflops"]
+        # how much vector-ALU work the matrix pipe hides: the same loop on zero operands (full clock) with n independent FMAs per MFMA
+        zero_ops = torch.zeros(8192, dtype=torch.bfloat16, device="cuda")
+        for n in (0, 2, 4, 6, 8):
+            fl = [0.0]
+
+            def vprobe():
+                fl[0] = sk.skiparse_mfma_valu_probe(zero_ops, sink, n, 512, 100000)
+
+            v_ms = time_calls(vprobe, 3, 1)
+            extras[f"mfma_zero_operands_with_{n}_fma_per_mfma_tflops"] = round(fl[0] / v_ms / 1e9, 1)
         del sink
     it = max(3, min(10, args.steps))
     out8 = None

@@ -158,6 +158,14 @@ int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const 
 int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int dtype, int blocks, int iters,
                         double* flop, void* stream);
 
+/*
+ * Measurement aid: the bf16 MFMA loop (iters * 2 instructions per wavefront) with valu_per_mfma (0, 2, 4, 6 or 8) independent
+ * v_fma_f32 after every MFMA.  Timed by the benchmark to show how much vector-ALU work the matrix pipe hides on this chip, which
+ * is what limits a softmax fused between two matrix products.  Buffers as for skiparse_mfma_probe.
+ */
+int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
+                             int iters, double* flop, void* stream);
+
 /* Text for an error code; never NULL. */
 const char* skiparse_strerror(int code);
 

@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.skiparse_attn_fwd_fp8.argtypes = [vp] * 7 + [i] * 8 + [f, vp]
         L.skiparse_mfma_probe.restype = i
         L.skiparse_mfma_probe.argtypes = [vp, sz, vp, sz, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
+        L.skiparse_mfma_valu_probe.restype = i
+        L.skiparse_mfma_valu_probe.argtypes = [vp, sz, vp, sz, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
         L.skiparse_strerror.restype = ctypes.c_char_p
         L.skiparse_strerror.argtypes = [i]
         L.skiparse_last_hip_error.restype = i
@@ -282,5 +284,16 @@ def skiparse_mfma_probe(operands: torch.Tensor, sink: torch.Tensor, fp8: bool, b
         lib().skiparse_mfma_probe(_dev(operands, "operands"), operands.numel() * operands.element_size(), _dev(sink, "sink"),
                                   sink.numel() * sink.element_size(), FP8_E4M3 if fp8 else BF16, blocks, iters, ctypes.byref(flop), _stream()),
         "skiparse_mfma_probe",
+    )
+    return flop.value
+
+
+def skiparse_mfma_valu_probe(operands: torch.Tensor, sink: torch.Tensor, valu_per_mfma: int, blocks: int, iters: int) -> float:
+    """Measurement aid: bf16 MFMA loop with `valu_per_mfma` independent FMAs after every MFMA; returns the FLOP of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(
+        lib().skiparse_mfma_valu_probe(_dev(operands, "operands"), operands.numel() * operands.element_size(), _dev(sink, "sink"),
+                                       sink.numel() * sink.element_size(), valu_per_mfma, blocks, iters, ctypes.byref(flop), _stream()),
+        "skiparse_mfma_valu_probe",
     )
     return flop.value

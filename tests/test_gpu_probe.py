@@ -22,3 +22,15 @@ def test_mfma_probe_runs_and_counts_flop():
     torch.cuda.synchronize()
     assert flop8 == 2.0 * 32 * 32 * 64 * 4 * 2 * 4 * 16
     assert bool((sink == 4 * 16 * 64 * 2).all())
+
+
+def test_mfma_valu_probe_runs():
+    import paper_2605_28691_amd as sk
+
+    ops = torch.zeros(8192, dtype=torch.bfloat16, device="cuda")
+    sink = torch.full((8 * 256,), -1.0, dtype=torch.float32, device="cuda")
+    for n in (0, 2, 4, 6, 8):
+        flop = sk.skiparse_mfma_valu_probe(ops, sink, n, 8, 5)
+        assert flop == 2.0 * 32 * 32 * 16 * 2 * 5 * 4 * 8
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
