@@ -54,6 +54,10 @@ def _load():
         lib.oracle_attention_bwd.argtypes = [vp] * 7 + [i64, i64, i, i, dbl, i]
         lib.oracle_skiparse_attention_bwd.restype = i
         lib.oracle_skiparse_attention_bwd.argtypes = [vp] * 7 + [i] * 8 + [dbl, i]
+        lib.oracle_skiparse_attention_bwd_padded.restype = i
+        lib.oracle_skiparse_attention_bwd_padded.argtypes = [vp] * 7 + [i] * 8 + [dbl, i]
+        lib.oracle_skiparse_attention_bwd_unit_padded.restype = i
+        lib.oracle_skiparse_attention_bwd_unit_padded.argtypes = [vp] * 5 + [i64] + [vp] * 3 + [i, i] + [i] * 8 + [dbl, i]
         lib.oracle_skiparse_attention_bwd_unit.restype = i
         lib.oracle_skiparse_attention_bwd_unit.argtypes = [vp] * 5 + [i64] + [vp] * 3 + [i, i, i64] + [i] * 8 + [dbl, i]
         lib.oracle_switch_pattern.restype = i
@@ -227,6 +231,41 @@ def skiparse_attention_bwd_unit(q, k, v, dout, b: int, head: int, toks, T: int, 
             int(toks[0]), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), code,
         ),
         "skiparse_attention_bwd_unit",
+    )
+    return dq, dk, dv
+
+
+def skiparse_attention_bwd_padded(q, k, v, dout, T: int, H: int, W: int, s: int, pattern: str, scale: float):
+    """Gradients (dq, dk, dv) in the any-resolution mode (mask form: real tokens of one class attend to each other; any H, W)."""
+    code = _dtype_code(q, k, v, dout)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    dq, dk, dv = (np.empty(q.shape, dtype=np.float64) for _ in range(3))
+    _check(
+        _load().oracle_skiparse_attention_bwd_padded(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), code
+        ),
+        "skiparse_attention_bwd_padded",
+    )
+    return dq, dk, dv
+
+
+def skiparse_attention_bwd_unit_padded(q, k, v, dout, b: int, head: int, toks, T: int, H: int, W: int, s: int, pattern: str, scale: float):
+    """Any-resolution mode: gradient rows (dq, dk, dv), each [len(toks)][D], for tokens of ONE class (that of toks[0]) of batch
+    element b and head `head`; walks the whole unit."""
+    code = _dtype_code(q, k, v, dout)
+    B, N, heads, D = q.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    toks = np.ascontiguousarray(np.asarray(toks, dtype=np.int64).reshape(-1))
+    dq, dk, dv = (np.empty((toks.shape[0], D), dtype=np.float64) for _ in range(3))
+    _check(
+        _load().oracle_skiparse_attention_bwd_unit_padded(
+            _ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(toks), toks.shape[0], _ptr(dq), _ptr(dk), _ptr(dv), int(b), int(head),
+            B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), code,
+        ),
+        "skiparse_attention_bwd_unit_padded",
     )
     return dq, dk, dv
 

@@ -652,6 +652,132 @@ int oracle_skiparse_attention_bwd_unit(const void *q, const void *k, const void 
 }
 
 /*
+ * Gradients in the any-resolution mode (Sec. 3.2), mask form as oracle_skiparse_attention_rows_padded: every real token
+ * attends to the real tokens of its own class and batch element, whatever H and W are; no padded copy exists, so the
+ * gradients are those of that masked attention.  The tokens of one class in raster order form one attention unit.
+ *   unit_only = 0: all units; dq, dk, dv = [B][N][heads][D] (float64, original layout).
+ *   unit_only = 1: only the unit of (b0, hd0, class of toks[0]); dq, dk, dv = [n_toks][D] for the listed tokens.
+ */
+static int bwd_padded_impl(const void *q, const void *k, const void *v, const void *dout, double *dq, double *dk, double *dv,
+                           int B, int heads, int T, int H, int W, int D, int s, int pattern, double scale, int dtype,
+                           int unit_only, int b0, int hd0, const int64_t *toks, int64_t n_toks)
+{
+    int64_t C = (int64_t)heads * D, N = (int64_t)T * H * W;
+    int p0 = 0, q0 = 0;
+    if (unit_only) class_of(pattern, s, H, W, toks[0], &p0, &q0);
+    int n_units = unit_only ? 1 : B * heads * s * s;
+    int fail = 0;
+    for (int u = 0; u < n_units && !fail; u++) {
+        int b = unit_only ? b0 : u / (heads * s * s), hd = unit_only ? hd0 : (u / (s * s)) % heads;
+        int pc = unit_only ? p0 : (u % (s * s)) / s, qc = unit_only ? q0 : u % s;
+        /* members of the class, raster order */
+        int64_t cnt = 0;
+        for (int64_t n = 0; n < N; n++) {
+            int pp, qq;
+            class_of(pattern, s, H, W, n, &pp, &qq);
+            cnt += (pp == pc && qq == qc);
+        }
+        if (cnt == 0) continue; /* a class with no real token */
+        int64_t *off = (int64_t *)malloc(sizeof(int64_t) * (size_t)cnt);
+        int64_t *acc_off = (int64_t *)malloc(sizeof(int64_t) * (size_t)cnt);
+        int64_t *tok = (int64_t *)malloc(sizeof(int64_t) * (size_t)cnt);
+        if (!off || !acc_off || !tok) {
+            free(off); free(acc_off); free(tok);
+            return -2;
+        }
+        int64_t m = 0;
+        for (int64_t n = 0; n < N; n++) {
+            int pp, qq;
+            class_of(pattern, s, H, W, n, &pp, &qq);
+            if (pp == pc && qq == qc) {
+                tok[m] = n;
+                off[m] = ((int64_t)b * N + n) * C + (int64_t)hd * D;
+                acc_off[m] = unit_only ? -1 : off[m];
+                m++;
+            }
+        }
+        if (unit_only) {
+            for (int64_t t = 0; t < n_toks; t++) {
+                int64_t pos = -1;
+                for (int64_t i = 0; i < cnt; i++)
+                    if (tok[i] == toks[t]) pos = i;
+                if (pos < 0 || acc_off[pos] >= 0) { free(off); free(acc_off); free(tok); return -1; } /* other class, or twice */
+                acc_off[pos] = t * D;
+            }
+        }
+        int64_t n_acc = unit_only ? n_toks * D : 0;
+#pragma omp parallel
+        {
+            double *p = (double *)malloc(sizeof(double) * (size_t)cnt);
+            double *ds = (double *)malloc(sizeof(double) * (size_t)cnt);
+            double *dq_row = (double *)malloc(sizeof(double) * (size_t)D);
+            /* private accumulators: the sampled mode keeps [n_toks][D]; the full mode accumulates the unit's own rows, which no
+               other unit touches, but threads of this unit do, so they also go through private copies of the unit's rows */
+            int64_t loc_n = unit_only ? n_acc : cnt * D;
+            double *dk_loc = (double *)calloc((size_t)loc_n, sizeof(double));
+            double *dv_loc = (double *)calloc((size_t)loc_n, sizeof(double));
+            int64_t *loc_off = (int64_t *)malloc(sizeof(int64_t) * (size_t)cnt);
+            if (!p || !ds || !dq_row || !dk_loc || !dv_loc || !loc_off) {
+#pragma omp atomic write
+                fail = 1;
+            } else {
+                for (int64_t i = 0; i < cnt; i++) loc_off[i] = unit_only ? acc_off[i] : i * D;
+#pragma omp for schedule(static)
+                for (int64_t i = 0; i < cnt; i++) {
+                    softmax_row(q, off[i], k, off, cnt, D, scale, dtype, p);
+                    bwd_row(q, off[i], k, v, dout, off, cnt, D, scale, dtype, p, ds, dq_row, dk_loc, dv_loc, loc_off);
+                    if (acc_off[i] >= 0)
+                        for (int d = 0; d < D; d++) dq[acc_off[i] + d] = dq_row[d];
+                }
+#pragma omp critical
+                for (int64_t i = 0; i < cnt; i++) {
+                    if (acc_off[i] < 0) continue;
+                    for (int d = 0; d < D; d++) {
+                        dk[acc_off[i] + d] += dk_loc[loc_off[i] + d];
+                        dv[acc_off[i] + d] += dv_loc[loc_off[i] + d];
+                    }
+                }
+            }
+            free(p); free(ds); free(dq_row); free(dk_loc); free(dv_loc); free(loc_off);
+        }
+        free(off); free(acc_off); free(tok);
+    }
+    return fail ? -2 : 0;
+}
+
+int oracle_skiparse_attention_bwd_padded(const void *q, const void *k, const void *v, const void *dout, double *dq, double *dk,
+                                         double *dv, int B, int heads, int T, int H, int W, int D, int s, int pattern,
+                                         double scale, int dtype)
+{
+    if (!q || !k || !v || !dout || !dq || !dk || !dv || B < 1 || heads < 1 || T < 1 || H < 1 || W < 1 || D < 1 || s < 1) return -1;
+    if (pattern != ORACLE_TOKEN && pattern != ORACLE_GROUP) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    size_t n = (size_t)B * T * H * W * heads * D;
+    memset(dq, 0, sizeof(double) * n);
+    memset(dk, 0, sizeof(double) * n);
+    memset(dv, 0, sizeof(double) * n);
+    return bwd_padded_impl(q, k, v, dout, dq, dk, dv, B, heads, T, H, W, D, s, pattern, scale, dtype, 0, 0, 0, NULL, 0);
+}
+
+int oracle_skiparse_attention_bwd_unit_padded(const void *q, const void *k, const void *v, const void *dout, const int64_t *toks,
+                                              int64_t n_toks, double *dq, double *dk, double *dv, int b, int hd, int B, int heads,
+                                              int T, int H, int W, int D, int s, int pattern, double scale, int dtype)
+{
+    if (!q || !k || !v || !dout || !toks || !dq || !dk || !dv || n_toks < 1 || B < 1 || heads < 1 || T < 1 || H < 1 || W < 1 ||
+        D < 1 || s < 1)
+        return -1;
+    if (pattern != ORACLE_TOKEN && pattern != ORACLE_GROUP) return -1;
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F64) return -1;
+    if (b < 0 || b >= B || hd < 0 || hd >= heads) return -1;
+    for (int64_t t = 0; t < n_toks; t++)
+        if (toks[t] < 0 || toks[t] >= (int64_t)T * H * W) return -1;
+    memset(dq, 0, sizeof(double) * (size_t)(n_toks * D));
+    memset(dk, 0, sizeof(double) * (size_t)(n_toks * D));
+    memset(dv, 0, sizeof(double) * (size_t)(n_toks * D));
+    return bwd_padded_impl(q, k, v, dout, dq, dk, dv, B, heads, T, H, W, D, s, pattern, scale, dtype, 1, b, hd, toks, n_toks);
+}
+
+/*
  * Quantise x (bf16 bit patterns, ORIGINAL layout [B][N][heads][D]) to E4M3 codes in the SPARSE layout
  * [s*s*B][Nsub][heads][D] with one float32 scale per (subsequence, head, block of 128 consecutive positions):
  *   amax  = max |x| over the block (all D channels);  scale = amax / 448, inv = 448 / amax  (both float32; 1 if amax = 0)

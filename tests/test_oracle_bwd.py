@@ -139,3 +139,41 @@ def test_unit_mode_matches_full_gradient(pattern):
     other = oracle.src_index(pattern, s, T, H, W, (p0 + 1) % s, q0, 0)
     with pytest.raises(ValueError):
         oracle.skiparse_attention_bwd_unit(q, k, v, dout, b, head, [n0, other], T, H, W, s, pattern, 0.5)
+
+
+@pytest.mark.parametrize("pattern", ["token", "group"])
+@pytest.mark.parametrize("B,heads,D,T,H,W,s", [(2, 2, 4, 2, 5, 7, 2), (1, 1, 3, 1, 7, 10, 3), (1, 2, 4, 1, 1, 1, 2)])
+def test_padded_bwd_matches_autograd_through_masked_dense_attention(B, heads, D, T, H, W, s, pattern):
+    """Any-resolution mode: grids that are not multiples of s*s.  The class mask needs no divisibility."""
+    N = T * H * W
+    q, k, v, dout = (_rand(B, N, heads, D) for _ in range(4))
+    got = oracle.skiparse_attention_bwd_padded(q, k, v, dout, T, H, W, s, pattern, 0.45)
+    want = _autograd_attention(q, k, v, dout, 0.45, mask=_class_mask(T, H, W, s, pattern))
+    for g, w_, name in zip(got, want, "qkv"):
+        np.testing.assert_allclose(g, w_, rtol=1e-9, atol=1e-11, err_msg=f"d{name}")
+
+
+@pytest.mark.parametrize("pattern", ["token", "group"])
+def test_padded_bwd_equals_plain_bwd_on_divisible_grids_and_unit_mode(pattern):
+    B, heads, D, T, H, W, s = 2, 2, 4, 2, 8, 4, 2
+    N = T * H * W
+    q, k, v, dout = (_rand(B, N, heads, D) for _ in range(4))
+    a = oracle.skiparse_attention_bwd_padded(q, k, v, dout, T, H, W, s, pattern, 0.5)
+    b = oracle.skiparse_attention_bwd(q, k, v, dout, T, H, W, s, pattern, 0.5)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, rtol=1e-11, atol=1e-13)
+    # one unit of a non-divisible grid against the full padded gradient
+    T, H, W = 2, 7, 9
+    N = T * H * W
+    q, k, v, dout = (_rand(B, N, heads, D) for _ in range(4))
+    full = oracle.skiparse_attention_bwd_padded(q, k, v, dout, T, H, W, s, pattern, 0.5)
+    mask = _class_mask(T, H, W, s, pattern)
+    n0 = 40
+    members = [int(n) for n in np.nonzero(mask[n0] == 0.0)[0]]
+    toks = [n0, members[0], members[-1]] if members[0] != n0 and members[-1] != n0 else [n0, members[1]]
+    got = oracle.skiparse_attention_bwd_unit_padded(q, k, v, dout, 1, 0, toks, T, H, W, s, pattern, 0.5)
+    for g, f in zip(got, full):
+        np.testing.assert_allclose(g, f[1, toks, 0], rtol=1e-10, atol=1e-13)
+    other = int(np.nonzero(mask[n0] != 0.0)[0][0])
+    with pytest.raises(ValueError):
+        oracle.skiparse_attention_bwd_unit_padded(q, k, v, dout, 1, 0, [n0, other], T, H, W, s, pattern, 0.5)
