@@ -269,6 +269,17 @@ def main() -> int:
                 real_flops += 4.0 * w.B * w.heads * float(n_c) ** 2 * w.D
         extras["pad720p_token_ms"] = round(pad_ms, 4)
         extras["pad720p_real_tflops"] = round(real_flops / pad_ms / 1e9, 2)
+        if "bwd" in sections:
+            # the paper's training grid (Sec. 4.1): backward in the any-resolution mode
+            dop = torch.randn(shp, generator=g, device="cuda", dtype=torch.bfloat16)
+            opl, lsep = sk.skiparse_attn_fwd_lse(qp, kp, vp, T, Hp_real, W, s, "token", scale=w.scale, out=op, pad=True)
+            gp = [torch.empty_like(qp) for _ in range(3)]
+            wsp = torch.empty(sk.skiparse_bwd_workspace_bytes(w.B, w.heads, T, Hp_real, W, w.D, s, "token", pad=True), dtype=torch.uint8, device="cuda")
+            pb_ms = time_calls(lambda: sk.skiparse_attn_bwd(qp, kp, vp, opl, dop, lsep, T, Hp_real, W, s, "token", scale=w.scale, dq=gp[0],
+                                                            dk=gp[1], dv=gp[2], workspace=wsp, pad=True), 3, 1)
+            extras["pad720p_bwd_ms"] = round(pb_ms, 4)
+            extras["pad720p_bwd_effective_real_tflops"] = round(2.5 * real_flops / pb_ms / 1e9, 2)
+            del dop, lsep, gp, wsp
         del qp, kp, vp, op
     if "dense_ms" in extras and "fused_group_ms" in extras:
         # the paper's 40-block model (Sec. 4.1): 8 full-attention blocks and 32 sparse ones, token-wise and group-wise alternating;

@@ -111,21 +111,25 @@ int skiparse_attn_fwd_sparse(const void* q, const void* k, const void* v, void* 
 /*
  * Training (Sec. 4.1: the model is fine-tuned with the sparse attention in place).
  * skiparse_attn_fwd_lse: the fused forward (as skiparse_attn_fwd with SKIPARSE_FUSED) that also writes, for the backward pass,
- *   lse[sb][head][j] = log sum_keys exp(scale q.k)  (natural log, float32, [s*s*B][heads][T*H*W/(s*s)]: subsequence order).
+ *   lse[sb][head][j] = log sum_keys exp(scale q.k)  (natural log, float32, subsequence order; skiparse_lse_bytes() bytes).
  * skiparse_attn_bwd: gradients of that layer for a loss with dL/dout = dout:
  *   dv = P^T dout,  dq = scale dS k,  dk = scale dS^T q,  dS = P o (dout v^T - rowsum(dout o out)),  P = exp(scale q k^T - lse),
  *   all inside every subsequence.  q, k, v, out, dout, dq, dk, dv: ORIGINAL layout [B][T*H*W][heads][head_dim] bf16; out and lse
- *   must be what skiparse_attn_fwd_lse produced for the same q, k, v, scale.  P and dS are rounded to bf16 for the matrix
- *   products, accumulation is fp32, the gradients are rounded to bf16.  Deterministic (no atomics).
- *   workspace: skiparse_bwd_workspace_bytes() bytes of device memory (one float per query and head).
+ *   must be what skiparse_attn_fwd_lse produced for the same q, k, v, scale and flags.  P and dS are rounded to bf16 for the
+ *   matrix products, accumulation is fp32, the gradients are rounded to bf16.  Deterministic (no atomics).
+ *   workspace: skiparse_bwd_workspace_bytes() bytes of device memory (one float per position and head).
  *   No gradient buffer may overlap any other argument.  s = 1 gives the gradients of full attention.
+ * flags: 0, or SKIPARSE_PAD for the any-resolution mode (Sec. 3.2; the paper trains at 720x1280, a grid that needs the padding):
+ *   H and W arbitrary, positions j then run over the grid padded to multiples of s*s (lse of a padding position is 0), padding
+ *   positions are masked keys and have no gradients.
  */
+size_t skiparse_lse_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, unsigned flags);
 int skiparse_attn_fwd_lse(const void* q, const void* k, const void* v, void* out, float* lse, int B, int heads, int T, int H, int W,
-                          int head_dim, int s, int pattern, float scale, int dtype, void* stream);
-size_t skiparse_bwd_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern);
+                          int head_dim, int s, int pattern, float scale, int dtype, unsigned flags, void* stream);
+size_t skiparse_bwd_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, unsigned flags);
 int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
                       void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
-                      int dtype, void* workspace, size_t workspace_bytes, void* stream);
+                      int dtype, unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * 8-bit variant (motivated by Sec. 3.5, which runs the attention MatMuls in an 8-bit format; here OCP fp8 e4m3

@@ -55,12 +55,14 @@ def lib() -> ctypes.CDLL:
         L.skiparse_attn_fwd.argtypes = [vp] * 4 + [i] * 8 + [f, i, u, vp, sz, vp]
         L.skiparse_attn_fwd_sparse.restype = i
         L.skiparse_attn_fwd_sparse.argtypes = [vp] * 4 + [i] * 9 + [f, i, vp]
+        L.skiparse_lse_bytes.restype = sz
+        L.skiparse_lse_bytes.argtypes = [i] * 8 + [u]
         L.skiparse_attn_fwd_lse.restype = i
-        L.skiparse_attn_fwd_lse.argtypes = [vp] * 5 + [i] * 8 + [f, i, vp]
+        L.skiparse_attn_fwd_lse.argtypes = [vp] * 5 + [i] * 8 + [f, i, u, vp]
         L.skiparse_bwd_workspace_bytes.restype = sz
-        L.skiparse_bwd_workspace_bytes.argtypes = [i] * 8
+        L.skiparse_bwd_workspace_bytes.argtypes = [i] * 8 + [u]
         L.skiparse_attn_bwd.restype = i
-        L.skiparse_attn_bwd.argtypes = [vp] * 9 + [i] * 8 + [f, i, vp, sz, vp]
+        L.skiparse_attn_bwd.argtypes = [vp] * 9 + [i] * 8 + [f, i, u, vp, sz, vp]
         L.skiparse_workspace_bytes.restype = sz
         L.skiparse_workspace_bytes.argtypes = [i] * 8 + [u]
         L.skiparse_quantize_fp8.restype = i
@@ -202,41 +204,49 @@ def skiparse_attn_fwd_sparse(q, k, v, T: int, H: int, W: int, s: int, pattern: s
     return out
 
 
+def skiparse_lse_shape(B, heads, T, H, W, D, s, pattern: str, pad: bool = False):
+    """Shape of the log-sum-exp tensor: [s*s*B][heads][positions per subsequence] (positions of the padded grid with pad=True)."""
+    n = int(lib().skiparse_lse_bytes(B, heads, T, H, W, D, s, PATTERNS[pattern], PAD if pad else 0)) // 4
+    if n == 0:
+        raise ValueError("grid does not fit the pattern (use pad=True for the any-resolution mode)")
+    return (s * s * B, heads, n // (s * s * B * heads))
+
+
 def skiparse_attn_fwd_lse(q, k, v, T: int, H: int, W: int, s: int, pattern: str, scale: float = 0.0,
-                          out: torch.Tensor | None = None, lse: torch.Tensor | None = None):
-    """Fused forward that also returns the log-sum-exp the backward pass needs: (out, lse), lse float32
-    [s*s*B][heads][N/s^2] in subsequence order."""
+                          out: torch.Tensor | None = None, lse: torch.Tensor | None = None, pad: bool = False):
+    """Fused forward that also returns the log-sum-exp the backward pass needs: (out, lse), lse float32 in subsequence order."""
     B, heads, D = _dims(q, T, H, W)
     if out is None:
         out = torch.empty_like(q)
     if lse is None:
-        lse = torch.empty((s * s * B, heads, (T * H * W) // (s * s)), dtype=torch.float32, device=q.device)
+        lse = torch.empty(skiparse_lse_shape(B, heads, T, H, W, D, s, pattern, pad), dtype=torch.float32, device=q.device)
     _check(
         lib().skiparse_attn_fwd_lse(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), _dev(lse, "lse"), B, heads, T, H, W, D, s,
-                                    PATTERNS[pattern], float(scale), _DTYPES[q.dtype], _stream()),
+                                    PATTERNS[pattern], float(scale), _DTYPES[q.dtype], PAD if pad else 0, _stream()),
         "skiparse_attn_fwd_lse",
     )
     return out, lse
 
 
-def skiparse_bwd_workspace_bytes(B, heads, T, H, W, D, s, pattern: str) -> int:
-    return int(lib().skiparse_bwd_workspace_bytes(B, heads, T, H, W, D, s, PATTERNS[pattern]))
+def skiparse_bwd_workspace_bytes(B, heads, T, H, W, D, s, pattern: str, pad: bool = False) -> int:
+    return int(lib().skiparse_bwd_workspace_bytes(B, heads, T, H, W, D, s, PATTERNS[pattern], PAD if pad else 0))
 
 
 def skiparse_attn_bwd(q, k, v, out, dout, lse, T: int, H: int, W: int, s: int, pattern: str, scale: float = 0.0,
-                      dq=None, dk=None, dv=None, workspace: torch.Tensor | None = None):
-    """Gradients (dq, dk, dv) of the Skiparse attention layer; out and lse come from skiparse_attn_fwd_lse.  A uint8 device
-    workspace of skiparse_bwd_workspace_bytes() bytes is allocated with torch if none is passed."""
+                      dq=None, dk=None, dv=None, workspace: torch.Tensor | None = None, pad: bool = False):
+    """Gradients (dq, dk, dv) of the Skiparse attention layer; out and lse come from skiparse_attn_fwd_lse (same pad flag).  A
+    uint8 device workspace of skiparse_bwd_workspace_bytes() bytes is allocated with torch if none is passed."""
     B, heads, D = _dims(q, T, H, W)
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(q) if dk is None else dk
     dv = torch.empty_like(q) if dv is None else dv
     if workspace is None:
-        workspace = torch.empty(max(skiparse_bwd_workspace_bytes(B, heads, T, H, W, D, s, pattern), 1), dtype=torch.uint8, device=q.device)
+        workspace = torch.empty(max(skiparse_bwd_workspace_bytes(B, heads, T, H, W, D, s, pattern, pad), 1), dtype=torch.uint8, device=q.device)
     _check(
         lib().skiparse_attn_bwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), _dev(dout, "dout"), _dev(lse, "lse"),
                                 _dev(dq, "dq"), _dev(dk, "dk"), _dev(dv, "dv"), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale),
-                                _DTYPES[q.dtype], _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
+                                _DTYPES[q.dtype], PAD if pad else 0, _dev(workspace, "workspace"),
+                                workspace.numel() * workspace.element_size(), _stream()),
         "skiparse_attn_bwd",
     )
     return dq, dk, dv

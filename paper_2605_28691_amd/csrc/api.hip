@@ -291,14 +291,27 @@ int skiparse_attn_fwd_sparse(const void* q, const void* k, const void* v, void* 
     return finish(launch_attn_bf16(a, (hipStream_t)stream));
 }
 
-int skiparse_attn_fwd_lse(const void* q, const void* k, const void* v, void* out, float* lse, int B, int heads, int T, int H, int W,
-                          int head_dim, int s, int pattern, float scale, int dtype, void* stream) {
+// floats in the log-sum-exp / delta arrays: one per (subsequence, head, position); positions run over the padded grid in the
+// any-resolution mode (sh.n_sub is then the padded count)
+static size_t lse_elems(int B, int heads, int s, const Shape& sh) { return (size_t)s * s * B * heads * sh.n_sub; }
+
+size_t skiparse_lse_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, unsigned flags) {
+    if (flags & ~(unsigned)SKIPARSE_PAD) return 0;
     Shape sh;
-    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    if (check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh, (flags & SKIPARSE_PAD) != 0 && s > 1) != SKIPARSE_OK) return 0;
+    return lse_elems(B, heads, s, sh) * sizeof(float);
+}
+
+int skiparse_attn_fwd_lse(const void* q, const void* k, const void* v, void* out, float* lse, int B, int heads, int T, int H, int W,
+                          int head_dim, int s, int pattern, float scale, int dtype, unsigned flags, void* stream) {
+    if (flags & ~(unsigned)SKIPARSE_PAD) return SKIPARSE_EINVAL;
+    const bool pad = (flags & SKIPARSE_PAD) != 0 && s > 1;
+    Shape sh;
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh, pad);
     if (rc != SKIPARSE_OK) return rc;
     if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
     if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
-    const size_t bytes = sh.elems * 2, lse_bytes = (size_t)B * sh.n_tok * heads * sizeof(float);
+    const size_t bytes = sh.elems * 2, lse_bytes = lse_elems(B, heads, s, sh) * sizeof(float);
     rc = check_attn_ranges(sh, W, 2);
     if (rc != SKIPARSE_OK) return rc;
     rc = check_attn_ptrs(q, k, v, out, bytes);
@@ -311,28 +324,28 @@ int skiparse_attn_fwd_lse(const void* q, const void* k, const void* v, void* out
     a.q = q; a.k = k; a.v = v; a.out = out;
     a.B = B; a.heads = heads; a.head_dim = head_dim;
     a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
-    a.g = make_gridmap(T, H, W, s, pattern);
-    a.pad = false;
+    a.g = make_gridmap(T, H, W, s, pattern, pad);
+    a.pad = pad;
     a.out_kind = OUT_AS_INPUT;
     a.lse = lse;
     return finish(launch_attn_bf16(a, (hipStream_t)stream));
 }
 
-size_t skiparse_bwd_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern) {
-    Shape sh;
-    if (check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh) != SKIPARSE_OK) return 0;
-    return align256((size_t)B * sh.n_tok * heads * sizeof(float));
+size_t skiparse_bwd_workspace_bytes(int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, unsigned flags) {
+    return align256(skiparse_lse_bytes(B, heads, T, H, W, head_dim, s, pattern, flags));
 }
 
 int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
                       void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
-                      int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+                      int dtype, unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
+    if (flags & ~(unsigned)SKIPARSE_PAD) return SKIPARSE_EINVAL;
+    const bool pad = (flags & SKIPARSE_PAD) != 0 && s > 1;
     Shape sh;
-    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh, pad);
     if (rc != SKIPARSE_OK) return rc;
     if (elem_size(dtype) == 0) return SKIPARSE_EINVAL;
     if (dtype != SKIPARSE_BF16 || (head_dim != 64 && head_dim != 128)) return SKIPARSE_EUNSUPPORTED;
-    const size_t bytes = sh.elems * 2, lse_bytes = (size_t)B * sh.n_tok * heads * sizeof(float);
+    const size_t bytes = sh.elems * 2, lse_bytes = lse_elems(B, heads, s, sh) * sizeof(float);
     rc = check_attn_ranges(sh, W, 2);
     if (rc != SKIPARSE_OK) return rc;
     const void* ins[5] = {q, k, v, out, dout};
@@ -361,7 +374,8 @@ int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* o
     a.dq = dq; a.dk = dk; a.dv = dv;
     a.B = B; a.heads = heads; a.head_dim = head_dim;
     a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
-    a.g = make_gridmap(T, H, W, s, pattern);
+    a.pad = pad;
+    a.g = make_gridmap(T, H, W, s, pattern, pad);
     return finish(launch_attn_bwd_bf16(a, (hipStream_t)stream));
 }
 

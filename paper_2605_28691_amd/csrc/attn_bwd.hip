@@ -43,7 +43,9 @@ constexpr int BNW = 8;             // wavefronts per workgroup: 256 owners share
 constexpr int BNT = 64 * BNW;
 constexpr float LOG2E = 1.4426950408889634f;
 
-template <int D, int MODE>
+// PAD: any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s; a padding position is skipped as an
+// owner and contributes nothing as a streamed row (a -inf logit bias in the dQ launch, a +inf log-sum-exp in the other two).
+template <int D, int MODE, bool PAD>
 __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_tiles, uint32_t total, uint32_t per_xcd) {
     constexpr int KS = D / 16;   // MFMA steps along head_dim
     constexpr int MT = D / 32;   // 32-channel blocks of the gradient row
@@ -92,9 +94,17 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 
     // ---- owner row: operands in registers (B operands: lane = owner lq, 8 consecutive channels starting at 16*ks + 8*h)
     const uint32_t jo = ot * (32u * BNW) + wave * 32u + lq;
-    const bool own_valid = jo < n_seq;
-    const uint32_t jo_c = own_valid ? jo : n_seq - 1u;
-    const size_t own_off = (size_t)src_token(a.g, p, q, jo_c) * C;
+    // token at position j of this unit and whether it is a real one (always, outside the any-resolution mode)
+    auto token_at = [&](uint32_t j, bool* real) __attribute__((always_inline)) -> uint32_t {
+        if (PAD) return src_token_padded(a.g, p, q, j, real);
+        *real = true;
+        return src_token(a.g, p, q, j);
+    };
+    const uint32_t jo_c = jo < n_seq ? jo : n_seq - 1u;
+    bool own_real;
+    const uint32_t own_tok = token_at(jo_c, &own_real);
+    const bool own_valid = jo < n_seq && own_real;
+    const size_t own_off = (size_t)(own_real ? own_tok : 0u) * C;  // a padding owner reads token 0 and stores nothing
     bf16x8 own1[KS], own2[TWO ? KS : 1];
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
@@ -124,20 +134,29 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 #pragma unroll
         for (int i = 0; i < IPW; i++) {
             const uint32_t j = t * BT + st_row[i];
-            const size_t off = (size_t)src_token(a.g, p, q, j < n_seq ? j : n_seq - 1u) * C * 2 + st_cb[i];  // bytes
+            bool real;
+            const uint32_t tok = token_at(j < n_seq ? j : n_seq - 1u, &real);
+            const size_t off = (size_t)(real ? tok : 0u) * C * 2 + st_cb[i];  // bytes; padding rows read token 0
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st1_g + off),
                                              (LDS_PTR(void))(b1 + (wave * IPW + i) * 1024u), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st2_g + off),
                                              (LDS_PTR(void))(b2 + (wave * IPW + i) * 1024u), 16, 0, 0);
         }
-        if (MODE != BWD_DQ && tid < BT) {  // per-query values of the streamed rows; rows past the end contribute nothing
+        if ((MODE != BWD_DQ || PAD) && tid < BT) {  // per-row values of the streamed rows; rows past the end contribute nothing
             const uint32_t jj = t * BT + tid;
-            rl = jj < n_seq ? lse_u[jj] * LOG2E : INFINITY;
-            rd = (MODE == BWD_DK && jj < n_seq) ? delta_u[jj] : 0.f;
+            bool real = true;
+            if (PAD) (void)token_at(jj < n_seq ? jj : n_seq - 1u, &real);
+            const bool ok = jj < n_seq && real;
+            if (MODE == BWD_DQ) {
+                rl = ok ? 0.f : -INFINITY;  // streamed keys: a logit bias
+            } else {
+                rl = ok ? lse_u[jj] * LOG2E : INFINITY;  // streamed queries: P = exp2(s*c - L) = 0 for L = +inf
+                rd = (MODE == BWD_DK && ok) ? delta_u[jj] : 0.f;
+            }
         }
     };
     auto store_rowvals = [&](uint32_t buf) __attribute__((always_inline)) {
-        if (MODE != BWD_DQ && tid < BT) {
+        if ((MODE != BWD_DQ || PAD) && tid < BT) {
             row_l[buf][tid] = rl;
             row_d[buf][tid] = rd;
         }
@@ -186,7 +205,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
         const char* t2 = PARITY ? s2buf1 : s2buf0;
         const bool more = t + 1 < n_t;
         if (more) issue_tile(t + 1, PARITY ? s1buf0 : s1buf1, PARITY ? s2buf0 : s2buf1);
-        const bool tail = MODE == BWD_DQ && !more && (n_seq % BT) != 0;  // dQ: streamed keys past the end are masked
+        const bool tail = MODE == BWD_DQ && !PAD && !more && (n_seq % BT) != 0;  // dQ: streamed keys past the end are masked
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {
             f32x16 m1, m2;
@@ -209,7 +228,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             }
             // register r of a block is streamed row 8*(r/4) + 4*h + r%4
             f32x4 sl[4], sd[4];
-            if (MODE != BWD_DQ) {
+            if (MODE != BWD_DQ || PAD) {
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
                     sl[g] = *(const f32x4*)&row_l[PARITY][blk * 32 + 8 * g + 4 * h];
@@ -226,7 +245,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 #pragma unroll
                     for (int u = 0; u < 2; u++) {
                         const int r = g2 * 8 + e + u;
-                        const float l2 = MODE == BWD_DQ ? own_l : sl[r >> 2][r & 3];
+                        const float l2 = MODE != BWD_DQ ? sl[r >> 2][r & 3] : PAD ? own_l - sl[r >> 2][r & 3] : own_l;
                         float pr = __builtin_amdgcn_exp2f(fmaf(m1[r], c, -l2));
                         if (tail) {
                             const uint32_t row = t * BT + blk * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
@@ -279,7 +298,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 }
 
 // delta[unit][j] = sum_d dO[row][head][d] * O[row][head][d]: one wavefront per position (sb, j), D/8 lanes per head.
-template <int D>
+template <int D, bool PAD>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                                                         float* __restrict__ delta, GridMap g, int B, int heads, uint32_t n_rows) {
     constexpr int LPH = D / 8;        // lanes per head (16 bytes each)
@@ -297,11 +316,13 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
         q = pq - p * (uint32_t)g.s;
     }
     const size_t C = (size_t)heads * D;
-    const size_t base = ((size_t)b0 * (uint32_t)g.n_tok + src_token(g, p, q, j)) * C;
+    bool real = true;
+    const uint32_t tok = PAD ? src_token_padded(g, p, q, j, &real) : src_token(g, p, q, j);
+    const size_t base = ((size_t)b0 * (uint32_t)g.n_tok + (real ? tok : 0u)) * C;
     for (uint32_t h0 = 0; h0 < (uint32_t)heads; h0 += HPP) {
         const uint32_t head = h0 + lane / LPH;
         float sum = 0.f;
-        if (head < (uint32_t)heads) {
+        if (head < (uint32_t)heads && real) {  // a padding position gets delta = 0
             const size_t off = base + (size_t)head * D + (lane % LPH) * 8;
             const bf16x8 o = *(const bf16x8*)(out + off);
             const bf16x8 d = *(const bf16x8*)(dout + off);
@@ -314,7 +335,7 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
     }
 }
 
-template <int D, int MODE>
+template <int D, int MODE, bool PAD>
 static hipError_t launch_mode(const BwdArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
@@ -322,25 +343,25 @@ static hipError_t launch_mode(const BwdArgs& a, hipStream_t stream) {
     const uint64_t total = (uint64_t)n_units * o_tiles;
     if (total > 0x7ffffff0ull) return hipErrorInvalidConfiguration;
     const uint32_t per_xcd = (uint32_t)((total + 7u) / 8u);
-    attn_bwd_kernel<D, MODE><<<8u * per_xcd, BNT, 0, stream>>>(a, o_tiles, (uint32_t)total, per_xcd);
+    attn_bwd_kernel<D, MODE, PAD><<<8u * per_xcd, BNT, 0, stream>>>(a, o_tiles, (uint32_t)total, per_xcd);
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool PAD>
 static hipError_t launch_all(const BwdArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_rows = (uint32_t)a.B * s2 * (uint32_t)a.g.n_sub;
-    bwd_delta_kernel<D><<<(n_rows + 3u) / 4u, 256, 0, stream>>>((const __bf16*)a.out, (const __bf16*)a.dout, a.delta, a.g, a.B, a.heads, n_rows);
+    bwd_delta_kernel<D, PAD><<<(n_rows + 3u) / 4u, 256, 0, stream>>>((const __bf16*)a.out, (const __bf16*)a.dout, a.delta, a.g, a.B, a.heads, n_rows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if ((e = launch_mode<D, BWD_DQ>(a, stream)) != hipSuccess) return e;
-    if ((e = launch_mode<D, BWD_DK>(a, stream)) != hipSuccess) return e;
-    return launch_mode<D, BWD_DV>(a, stream);
+    if ((e = launch_mode<D, BWD_DQ, PAD>(a, stream)) != hipSuccess) return e;
+    if ((e = launch_mode<D, BWD_DK, PAD>(a, stream)) != hipSuccess) return e;
+    return launch_mode<D, BWD_DV, PAD>(a, stream);
 }
 
 hipError_t launch_attn_bwd_bf16(const BwdArgs& a, hipStream_t stream) {
-    if (a.head_dim == 128) return launch_all<128>(a, stream);
-    if (a.head_dim == 64) return launch_all<64>(a, stream);
+    if (a.head_dim == 128) return a.pad ? launch_all<128, true>(a, stream) : launch_all<128, false>(a, stream);
+    if (a.head_dim == 64) return a.pad ? launch_all<64, true>(a, stream) : launch_all<64, false>(a, stream);
     return hipErrorInvalidValue;
 }
 

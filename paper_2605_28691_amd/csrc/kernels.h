@@ -59,6 +59,7 @@ struct BwdArgs {
     int heads;
     int head_dim;
     float scale;
+    bool pad;           // any-resolution mode: g describes the padded grid; padding positions are masked keys and skipped rows
     GridMap g;
 };
 hipError_t launch_attn_bwd_bf16(const BwdArgs& a, hipStream_t stream);

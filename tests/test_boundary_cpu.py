@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
             "skiparse_switch_pattern", "skiparse_attn_fwd_sparse", "skiparse_attn_fwd_lse",
-            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_mfma_probe", "skiparse_mfma_valu_probe"} <= set(names)
+            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes", "skiparse_mfma_probe", "skiparse_mfma_valu_probe"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -154,12 +154,16 @@ def test_attn_fwd_sparse_rejects_bad_arguments(lib):
 def test_backward_rejects_bad_arguments(lib):
     a = [ctypes.c_void_p(FAKE + i * (1 << 30)) for i in range(11)]
     f = ctypes.c_float(0.0)
-    need = lib.skiparse_bwd_workspace_bytes(1, 2, 2, 8, 8, 64, 2, 0)
+    need = lib.skiparse_bwd_workspace_bytes(1, 2, 2, 8, 8, 64, 2, 0, 0)
     assert need == 1 * 128 * 2 * 4  # one float per query and head (already a multiple of 256)
-    assert lib.skiparse_bwd_workspace_bytes(1, 2, 2, 7, 8, 64, 2, 0) == 0  # bad shape
+    assert lib.skiparse_lse_bytes(1, 2, 2, 8, 8, 64, 2, 0, 0) == need
+    assert lib.skiparse_bwd_workspace_bytes(1, 2, 2, 7, 8, 64, 2, 0, 0) == 0  # bad shape
+    # any-resolution mode: positions of the grid padded to multiples of s*s = 4: 2 x 8 x 8 again
+    assert lib.skiparse_lse_bytes(1, 2, 2, 7, 6, 64, 2, 0, 2) == need
+    assert lib.skiparse_lse_bytes(1, 2, 2, 7, 6, 64, 2, 0, 1) == 0  # unknown flag
 
-    def bwd(ptrs, ws=a[9], ws_bytes=need, H=8, D=64, dtype=0):
-        return lib.skiparse_attn_bwd(*ptrs, 1, 2, 2, H, 8, D, 2, 0, f, dtype, ws, ws_bytes, None)
+    def bwd(ptrs, ws=a[9], ws_bytes=need, H=8, D=64, dtype=0, flags=0):
+        return lib.skiparse_attn_bwd(*ptrs, 1, 2, 2, H, 8, D, 2, 0, f, dtype, flags, ws, ws_bytes, None)
 
     ok = a[:9]
     assert bwd([None] + ok[1:]) == -1
@@ -169,12 +173,13 @@ def test_backward_rejects_bad_arguments(lib):
     assert bwd(ok, ws_bytes=need - 1) == -4
     assert bwd(ok, ws=ok[8]) == -1                     # workspace aliases dv
     assert bwd(ok, H=7) == -2
+    assert bwd(ok, flags=1) == -1                      # only SKIPARSE_PAD is a flag here
     assert bwd(ok, D=96) == -3
     assert bwd(ok, dtype=1) == -3
     # forward with log-sum-exp
-    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], None, 1, 2, 2, 8, 8, 64, 2, 0, f, 0, None) == -1
-    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], a[3], 1, 2, 2, 8, 8, 64, 2, 0, f, 0, None) == -1  # lse aliases out
-    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], a[4], 1, 2, 2, 8, 6, 64, 2, 1, f, 0, None) == -2  # group-wise needs W % 4 == 0
+    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], None, 1, 2, 2, 8, 8, 64, 2, 0, f, 0, 0, None) == -1
+    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], a[3], 1, 2, 2, 8, 8, 64, 2, 0, f, 0, 0, None) == -1  # lse aliases out
+    assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], a[4], 1, 2, 2, 8, 6, 64, 2, 1, f, 0, 0, None) == -2  # group-wise needs W % 4 == 0
 
 
 def test_mfma_probe_rejects_bad_arguments(lib):

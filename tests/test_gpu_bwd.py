@@ -141,3 +141,74 @@ def test_backward_480p_one_unit_and_invariants():
         dk_abs = dk[0, idx].double().abs().sum(0)
         assert float((dk_sum.abs() / dk_abs).max()) <= 2e-2     # cancels up to the bf16 rounding of the rows
         assert float((dv_sum - do_sum).abs().max()) <= 2e-2 * float(do_sum.abs().max())
+
+
+PAD_CASES = [  # B, heads, D, T, H, W, s -- any-resolution mode: H or W not a multiple of s*s
+    (1, 2, 128, 3, 5, 7, 2),
+    (2, 3, 128, 4, 10, 13, 2),   # padded grid 12 x 16: Nsub_pad = 192
+    (1, 2, 64, 5, 6, 30, 2),
+    (1, 4, 128, 2, 11, 20, 3),   # s = 3: padded to 18 x 27
+    (1, 2, 128, 9, 17, 21, 2),   # Nsub_pad = 9 * 5 * 6 = 270: two owner tiles, padding rows inside and at the end of tiles
+    (1, 1, 128, 9, 1, 33, 2),    # H = 1: the classes with p = 1 hold padding only
+    (1, 2, 128, 6, 8, 12, 2),    # divisible: must agree bit for bit with the plain mode
+]
+
+
+@pytest.mark.parametrize("B,heads,D,T,H,W,s", PAD_CASES)
+@pytest.mark.parametrize("pattern", ["token", "group"])
+def test_backward_any_resolution_small(B, heads, D, T, H, W, s, pattern):
+    """Sec. 3.2's padding + mask in the backward pass, against the oracle's mask-form gradients."""
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("bwd_pad", B, heads, D, T, H, W, s, seed=50 + s)
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    want = oracle.skiparse_attention_bwd_padded(*oracle_inputs(q, k, v), si.as_oracle_array(dout), T, H, W, s, pattern, w.scale)
+    qg, kg, vg, dg = (t.cuda() for t in (q, k, v, dout))
+    out, lse = sk.skiparse_attn_fwd_lse(qg, kg, vg, T, H, W, s, pattern, scale=w.scale, pad=True)
+    assert torch.equal(out, sk.skiparse_attn_fwd(qg, kg, vg, T, H, W, s, pattern, scale=w.scale, fused=True, pad=True))
+    n = q.numel()
+    guard = 4096
+    buf = torch.full((3, n + 2 * guard), 7.0, dtype=torch.bfloat16, device="cuda")  # canaries around every gradient
+    views = [buf[i, guard : guard + n].view(q.shape) for i in range(3)]
+    sk.skiparse_attn_bwd(qg, kg, vg, out, dg, lse, T, H, W, s, pattern, scale=w.scale, dq=views[0], dk=views[1], dv=views[2], pad=True)
+    assert bool((buf[:, :guard] == 7.0).all()) and bool((buf[:, guard + n :] == 7.0).all())
+    for g, wnt, name in zip(views, want, ("dq", "dk", "dv")):
+        assert_grad_close(to_np64(g), wnt, f"padded {pattern} {name}")
+    if H % (s * s) == 0 and W % (s * s) == 0:
+        _, lse0, *plain = _run(sk, q, k, v, dout, T, H, W, s, pattern, w.scale)
+        assert torch.equal(lse, lse0)
+        for g, p in zip(views, plain):
+            assert torch.equal(g, p)
+
+
+def test_backward_720p_one_unit():
+    """The paper's training grid (Sec. 4.1: 720 x 1280, latent 21 x 45 x 80, padded to 21 x 48 x 80), 8 of the 40 heads:
+    gradients of sampled tokens of one unit per pattern against the oracle, and the invariants over every unit."""
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("720p_bwd", 1, 8, 128, 21, 45, 80, 2, seed=11)
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    T, H, W, s = w.T, w.H, w.W, w.s
+    qg, kg, vg, dg = (t.cuda() for t in (q, k, v, dout))
+    n = np.arange(T * H * W)
+    hh, ww = (n // W) % H, n % W
+    for pattern in ("token", "group"):
+        out, lse = sk.skiparse_attn_fwd_lse(qg, kg, vg, T, H, W, s, pattern, scale=w.scale, pad=True)
+        dq, dk, dv = sk.skiparse_attn_bwd(qg, kg, vg, out, dg, lse, T, H, W, s, pattern, scale=w.scale, pad=True)
+        cls = (hh % s) * s + (ww % s) if pattern == "token" else ((hh // s) % s) * s + ((ww // s) % s)  # Sec. 3.1
+        b, head, n0 = 0, 3, 44 * W + 79 + 5 * H * W  # last row and column of a frame: next to the padding
+        members = np.nonzero(cls == cls[n0])[0]
+        toks = [int(n0)] + [int(members[i]) for i in (0, 1, len(members) // 2, len(members) - 1) if members[i] != n0]
+        want = oracle.skiparse_attention_bwd_unit_padded(*oracle_inputs(q, k, v), si.as_oracle_array(dout), b, head, toks, T, H, W, s,
+                                                         pattern, w.scale)
+        for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+            assert_grad_close(to_np64(g[b, toks, head]), wnt, f"720p {pattern} {name}")
+        for c in range(s * s):
+            idx = torch.tensor(np.nonzero(cls == c)[0], device="cuda")
+            dk_sum, dv_sum, do_sum = (x[0, idx].double().sum(0) for x in (dk, dv, dg))
+            dk_abs = dk[0, idx].double().abs().sum(0)
+            assert float((dk_sum.abs() / dk_abs).max()) <= 2e-2
+            assert float((dv_sum - do_sum).abs().max()) <= 2e-2 * float(do_sum.abs().max())
+        del out, lse, dq, dk, dv
