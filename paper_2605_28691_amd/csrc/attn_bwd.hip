@@ -42,6 +42,9 @@ constexpr int BT = 64;             // streamed rows per tile
 constexpr int BNW = 8;             // wavefronts per workgroup: 256 owners share every streamed tile
 constexpr int BNT = 64 * BNW;
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr int BRING_AHEAD = BNW;   // row offsets are formed this many tiles ahead, by one wavefront per tile in turn
+constexpr int BRING = 16;          // tiles of row offsets kept in LDS
+static_assert((BNW & (BNW - 1)) == 0 && (BRING & (BRING - 1)) == 0 && BRING >= BRING_AHEAD + 4, "ring sizes");
 
 // PAD: any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s; a padding position is skipped as an
 // owner and contributes nothing as a streamed row (a -inf logit bias in the dQ launch, a +inf log-sum-exp in the other two).
@@ -64,6 +67,8 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     __shared__ __attribute__((aligned(1024))) char s2buf1[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) float row_l[2][BT];  // dK, dV: log2-domain log-sum-exp of the streamed queries
     __shared__ __attribute__((aligned(16))) float row_d[2][BT];  // dK: their delta
+    __shared__ __attribute__((aligned(16))) uint32_t rowoff[BRING][BT];     // byte offsets of the streamed rows of the next tiles
+    __shared__ __attribute__((aligned(16))) unsigned char rowok[BRING][BT]; // PAD only: 1 = the row is a real token
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
@@ -123,30 +128,44 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     // which keeps the 16-byte fragment reads (16 consecutive rows) and the transposing reads (4 consecutive rows of 64 bytes)
     // both free of bank conflicts, so a tile that is read both ways is kept once.
     auto swz = [](uint32_t r) __attribute__((always_inline)) -> uint32_t { return lds_swizzle<D>(r); };
+    // The byte offsets of the streamed rows (relative to the unit's base; they fit 32 bits: checked on the host) come from a small
+    // ring in LDS filled BRING_AHEAD tiles ahead: for every tile ONE wavefront (they take turns) evaluates the index map for the 64
+    // rows of a tile, lane = row, and every lane later picks up the offsets of the rows it fetches.
+    const uint32_t row_bytes = (uint32_t)C * 2u;
+    auto produce = [&](uint32_t tile) __attribute__((always_inline)) {
+        const uint32_t j = tile * BT + lane;
+        bool real;
+        const uint32_t tok = token_at(j < n_seq ? j : n_seq - 1u, &real);  // rows past the end repeat the last row
+        rowoff[tile % BRING][lane] = real ? tok * row_bytes : 0u;          // padding rows read token 0
+        if (PAD) rowok[tile % BRING][lane] = real ? 1 : 0;
+    };
     uint32_t st_row[IPW], st_cb[IPW];
 #pragma unroll
     for (int i = 0; i < IPW; i++) {
         st_row[i] = (wave * IPW + i) * RPI + lane / CH;
         st_cb[i] = ((lane % CH) ^ swz(st_row[i])) * 16u;
     }
+    struct RowOffs {
+        uint32_t off[IPW];  // row offset + chunk offset of the lane's fetches of one tile (the same for both streamed tensors)
+    };
+    auto read_offs = [&](uint32_t tile) __attribute__((always_inline)) -> RowOffs {
+        RowOffs o;
+#pragma unroll
+        for (int i = 0; i < IPW; i++) o.off[i] = rowoff[tile % BRING][st_row[i]] + st_cb[i];
+        return o;
+    };
     float rl = 0.f, rd = 0.f;
-    auto issue_tile = [&](uint32_t t, char* b1, char* b2) __attribute__((always_inline)) {
+    auto issue_tile = [&](uint32_t t, const RowOffs& o, char* b1, char* b2) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < IPW; i++) {
-            const uint32_t j = t * BT + st_row[i];
-            bool real;
-            const uint32_t tok = token_at(j < n_seq ? j : n_seq - 1u, &real);
-            const size_t off = (size_t)(real ? tok : 0u) * C * 2 + st_cb[i];  // bytes; padding rows read token 0
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st1_g + off),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st1_g + o.off[i]),
                                              (LDS_PTR(void))(b1 + (wave * IPW + i) * 1024u), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st2_g + off),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st2_g + o.off[i]),
                                              (LDS_PTR(void))(b2 + (wave * IPW + i) * 1024u), 16, 0, 0);
         }
         if ((MODE != BWD_DQ || PAD) && tid < BT) {  // per-row values of the streamed rows; rows past the end contribute nothing
             const uint32_t jj = t * BT + tid;
-            bool real = true;
-            if (PAD) (void)token_at(jj < n_seq ? jj : n_seq - 1u, &real);
-            const bool ok = jj < n_seq && real;
+            const bool ok = jj < n_seq && (!PAD || rowok[t % BRING][tid] != 0);
             if (MODE == BWD_DQ) {
                 rl = ok ? 0.f : -INFINITY;  // streamed keys: a logit bias
             } else {
@@ -193,18 +212,25 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
         }
 
     const uint32_t n_t = (n_seq + BT - 1) / BT;
-    issue_tile(0, s1buf0, s2buf0);
+    produce(wave);  // tiles 0 .. BRING_AHEAD-1
+    __syncthreads();
+    issue_tile(0, read_offs(0), s1buf0, s2buf0);
+    RowOffs off_next = read_offs(1);
     store_rowvals(0);
     tile_landed();
     __syncthreads();
     // one tile: enqueue the loads of the next tile into the other buffers, compute on this one, wait, barrier.  The parity of
-    // the tile (which buffers) is a compile-time constant.
+    // the tile (which buffers) is a compile-time constant.  Tile t also forms the row offsets of tile t + BRING_AHEAD (written
+    // here, first read in tile t + BRING_AHEAD - 2; the slot's previous tenant, tile t + BRING_AHEAD - BRING, was last read in tile
+    // t + BRING_AHEAD - BRING - 1: barriers lie between in both directions).
     auto do_tile = [&](auto PARC, uint32_t t) __attribute__((always_inline)) {
         constexpr int PARITY = decltype(PARC)::value;  // t & 1
         const char* t1 = PARITY ? s1buf1 : s1buf0;
         const char* t2 = PARITY ? s2buf1 : s2buf0;
         const bool more = t + 1 < n_t;
-        if (more) issue_tile(t + 1, PARITY ? s1buf0 : s1buf1, PARITY ? s2buf0 : s2buf1);
+        if (more) issue_tile(t + 1, off_next, PARITY ? s1buf0 : s1buf1, PARITY ? s2buf0 : s2buf1);
+        off_next = read_offs(t + 2u);  // picked up a tile early so that the LDS read is not waited for
+        if (wave == (t & (uint32_t)(BNW - 1))) produce(t + BRING_AHEAD);
         const bool tail = MODE == BWD_DQ && !PAD && !more && (n_seq % BT) != 0;  // dQ: streamed keys past the end are masked
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {

@@ -62,6 +62,9 @@ constexpr int KT = 64;          // keys per staged tile (two 32-key blocks)
 constexpr int NW = 8;            // wavefronts per workgroup: two per SIMD, all sharing one K/V tile in LDS
 constexpr int NTHREADS = 64 * NW;
 constexpr int ATTN_QT = 1;       // 32-query tiles per wavefront
+constexpr int RING_AHEAD = NW;   // row offsets are formed this many tiles ahead, by one wavefront per window in turn
+constexpr int RING = 16;         // tiles of row offsets (and key validity) kept in LDS: a slot is rewritten RING - RING_AHEAD windows after its last use
+static_assert((NW & (NW - 1)) == 0 && (RING & (RING - 1)) == 0 && RING >= RING_AHEAD + 4, "ring sizes");
 constexpr int LDS_AHEAD = 3;     // MFMA groups by which the LDS fragment reads run ahead in the steady state
 constexpr float RESCALE_LOG2 = 8.0f;  // the reference maximum is only raised when it grew by more than 2^8
 
@@ -100,7 +103,6 @@ __device__ inline size_t uniform(size_t x) {
     return ((size_t)uniform((uint32_t)(x >> 32)) << 32) | uniform((uint32_t)x);
 }
 
-// GROUP selects the group-wise index map (two extra divisions by s per staged row); token-wise and dense use GROUP = false.
 // PAD selects the any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s, padding positions
 // are masked as keys (a validity byte and a 0 / -inf logit bias per staged row in LDS) and skipped as queries.
 // Row of `out` for position j of subsequence sb of the input's sparse layout: the token's row in the original layout, or its
@@ -127,7 +129,7 @@ __device__ inline size_t scattered_row(const AttnArgs& a, uint32_t sb, uint32_t 
     return ((size_t)(p * s + q) * B + b) * (uint32_t)gi.n_sub + r * (W / s) + ws;
 }
 
-template <int D, int QT, bool GROUP, bool PAD>
+template <int D, int QT, bool PAD>
 __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_fwd_bf16_kernel(AttnArgs a, uint32_t q_tiles, uint32_t total, uint32_t per_xcd) {
     using TL = Tile<D>;
     constexpr int KS = D / 16;     // MFMA steps along head_dim for S^T = K Q^T
@@ -138,8 +140,9 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     __shared__ __attribute__((aligned(1024))) char kbuf1[TL::TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char vbuf0[TL::TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char vbuf1[TL::TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char kmask[4][KT];  // PAD only: 1 = real key, per row of the last 4 K tiles
-    __shared__ __attribute__((aligned(16))) float kbias[4][KT];          // PAD only: the same as a logit bias, 0 or -inf
+    __shared__ __attribute__((aligned(16))) uint32_t rowoff[RING][KT];        // byte offsets of the rows of the next tiles
+    __shared__ __attribute__((aligned(16))) unsigned char kmask[RING][KT];    // PAD only: 1 = real key, per row of a K tile
+    __shared__ __attribute__((aligned(16))) float kbias[RING][KT];            // PAD only: the same as a logit bias, 0 or -inf
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uniform(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
@@ -190,82 +193,50 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     // land at the instruction's LDS base + 16*l, so one instruction of a wavefront fills RPI whole rows).  A wavefront issues IPW
     // such instructions per tile; lane l fetches, for row l/CH of the instruction's rows, the chunk that the swizzle puts at
     // position l%CH.  The row addresses come from the index map.
-    // Byte offset of a row relative to the unit's base (fits 32 bits: checked on the host).  Tiles are visited in order, so
-    // (r, ws) = (j / Ws, j % Ws) of a lane's rows are advanced by 64 positions with adds and one wrap instead of being divided out
-    // again; the products use 24-bit multiplies (operands checked on the host).
-    const uint32_t Ws = a.g.ws.d, row_bytes = (uint32_t)C * 2u;
+    // Byte offsets of the rows relative to the unit's base (they fit 32 bits: checked on the host) come from a small ring in LDS
+    // that is filled RING_AHEAD tiles ahead: in every window ONE wavefront (they take turns) forms the 64 offsets of one tile, lane =
+    // row, straight from the index map, and every lane of the workgroup later picks up the offsets of the rows it fetches.  The
+    // index arithmetic thus costs each wavefront one evaluation per 8 tiles instead of one per tile and fetched row.
+    const uint32_t row_bytes = (uint32_t)C * 2u;
     const uint32_t last_off = PAD ? 0u : src_token(a.g, p, q, n_seq - 1u) * row_bytes;  // rows past the end read the last valid row
-    const uint32_t row_c = p * a.g.cmul, col_c = q * a.g.cmul;
-    uint32_t st_row[TL::IPW], st_r[TL::IPW], st_ws[TL::IPW], st_j[TL::IPW], st_cb[TL::IPW];
-    bool st_valid[TL::IPW];  // PAD: whether the row whose offset was formed last is a real token
+    auto produce = [&](uint32_t tile) __attribute__((always_inline)) {
+        const uint32_t j = tile * KT + lane, jc = j < n_seq ? j : n_seq - 1u;
+        uint32_t off;
+        if (PAD) {
+            bool real;
+            const uint32_t tok = src_token_padded(a.g, p, q, jc, &real);
+            const bool valid = j < n_seq && real;
+            off = valid ? tok * row_bytes : 0u;  // padding rows read token 0; their logits are masked
+            kmask[tile % RING][lane] = valid ? 1 : 0;
+            kbias[tile % RING][lane] = valid ? 0.f : -INFINITY;
+        } else {
+            off = j < n_seq ? src_token(a.g, p, q, jc) * row_bytes : last_off;
+        }
+        rowoff[tile % RING][lane] = off;
+    };
+    uint32_t st_row[TL::IPW], st_cb[TL::IPW];
 #pragma unroll
     for (int i = 0; i < TL::IPW; i++) {
-        st_row[i] = (wave * TL::IPW + i) * TL::RPI + lane / TL::CH;  // row of the tile (< 64 <= any range limit)
-        st_j[i] = st_row[i];
-        st_r[i] = a.g.ws.div(st_row[i]);
-        st_ws[i] = st_row[i] - st_r[i] * Ws;
+        st_row[i] = (wave * TL::IPW + i) * TL::RPI + lane / TL::CH;  // row of the tile
         st_cb[i] = ((lane % TL::CH) ^ TL::swz(st_row[i])) * 16u;  // byte offset, inside the row, of the chunk this lane fetches
-        st_valid[i] = true;
     }
-    auto row_off_now = [&](int i) __attribute__((always_inline)) -> uint32_t {
-        uint32_t row = mad24(st_r[i], a.g.a, row_c);
-        uint32_t w = mad24(st_ws[i], a.g.a, col_c);
-        if (GROUP) {
-            row = mad24(a.g.sdiv.div(st_r[i]), a.g.b, row);
-            w = mad24(a.g.sdiv.div(st_ws[i]), a.g.b, w);
-        }
-        if (PAD) {  // (row, w) are coordinates on the padded grid: row = t * H_pad + h
-            const uint32_t t = a.g.hpad.div(row), hh = row - t * a.g.hpad.d;
-            st_valid[i] = st_j[i] < n_seq && hh < (uint32_t)a.g.H_real && w < (uint32_t)a.g.W;
-            const uint32_t tok = mad24(mad24(t, (uint32_t)a.g.H_real, hh), (uint32_t)a.g.W, w);
-            return st_valid[i] ? mad24(tok, row_bytes, 0u) : 0u;  // padding rows read token 0; their logits are masked
-        }
-        const uint32_t off = mad24(mad24(row, (uint32_t)a.g.W, w), row_bytes, 0u);
-        return st_j[i] < n_seq ? off : last_off;
-    };
     struct RowOffs {
-        uint32_t off[TL::IPW];
-        bool valid[TL::IPW];
+        uint32_t off[TL::IPW];  // row offset + chunk offset of the lane's fetches of one tile (the same for K and V)
     };
-    auto offs_now = [&]() __attribute__((always_inline)) -> RowOffs {
+    auto read_offs = [&](uint32_t tile) __attribute__((always_inline)) -> RowOffs {
         RowOffs o;
 #pragma unroll
-        for (int i = 0; i < TL::IPW; i++) {
-            o.off[i] = row_off_now(i);
-            o.valid[i] = st_valid[i];
-        }
+        for (int i = 0; i < TL::IPW; i++) o.off[i] = rowoff[tile % RING][st_row[i]] + st_cb[i];
         return o;
-    };
-    auto offs_next = [&]() __attribute__((always_inline)) -> RowOffs {  // offsets of the next tile's rows; call once per tile, in order
-#pragma unroll
-        for (int i = 0; i < TL::IPW; i++) {
-            st_j[i] += KT;
-            st_r[i] += a.g.step_r;
-            st_ws[i] += a.g.step_w;
-            const bool wrap = st_ws[i] >= Ws;
-            st_ws[i] = wrap ? st_ws[i] - Ws : st_ws[i];
-            st_r[i] = wrap ? st_r[i] + 1u : st_r[i];
-        }
-        return offs_now();
     };
     // enqueue the loads of one tile; they are complete (visible in LDS after the next barrier) once tile_landed() has returned
     auto issue_tile = [&](const __bf16* g, char* buf, const RowOffs& o) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TL::IPW; i++)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)g + o.off[i] + st_cb[i]),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)g + o.off[i]),
                                              (LDS_PTR(void))(buf + (wave * TL::IPW + i) * 1024u), 16, 0, 0);
     };
-    auto issue_k = [&](uint32_t tile, char* buf, const RowOffs& o) __attribute__((always_inline)) {
-        if (PAD) {
-#pragma unroll
-            for (int i = 0; i < TL::IPW; i++)
-                if (lane % TL::CH == 0) {
-                    kmask[tile & 3u][st_row[i]] = o.valid[i] ? 1 : 0;
-                    kbias[tile & 3u][st_row[i]] = o.valid[i] ? 0.f : -INFINITY;
-                }
-        }
-        issue_tile(Kg, buf, o);
-    };
+    auto issue_k = [&](char* buf, const RowOffs& o) __attribute__((always_inline)) { issue_tile(Kg, buf, o); };
     auto issue_v = [&](char* buf, const RowOffs& o) __attribute__((always_inline)) { issue_tile(Vg, buf, o); };
     auto tile_landed = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
@@ -386,7 +357,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
                 if (PAD) {
 #pragma unroll
                     for (int i = 0; i < 4; i++) {  // keys 8*i + 4*h + 0..3 of the block: one dword of validity bytes
-                        const uint32_t m4 = *(const uint32_t*)&kmask[(blk >> 1) & 3u][(blk & 1u) * 32u + 8 * i + 4 * h];
+                        const uint32_t m4 = *(const uint32_t*)&kmask[(blk >> 1) % RING][(blk & 1u) * 32u + 8 * i + 4 * h];
 #pragma unroll
                         for (int e = 0; e < 4; e++) s[4 * i + e] = ((m4 >> (8 * e)) & 1u) ? s[4 * i + e] : -INFINITY;
                     }
@@ -457,7 +428,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         f32x4 bias[4];  // PAD: register r of the block is key 8*(r/4) + 4*h + r%4
         if (PAD) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) bias[i] = *(const f32x4*)&kbias[(blk >> 1) & 3u][(blk & 1u) * 32u + 8 * i + 4 * h];
+            for (int i = 0; i < 4; i++) bias[i] = *(const f32x4*)&kbias[(blk >> 1) % RING][(blk & 1u) * 32u + 8 * i + 4 * h];
         }
 #pragma unroll
         for (int g = 0; g < NG; g++) {
@@ -534,19 +505,24 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
 
     // Staging schedule.  Window W reads K tile W and V tile W-1 from LDS.  At its start it enqueues the direct loads of K tile
     // W+1 (into the K buffer that window W-1 read) and of V tile W (into the V buffer that window W-1 read); they have the whole
-    // window to land and are waited for just before the window's closing barrier.
-    // ---- prologue: K tile 0
-    RowOffs off_prev = offs_now();  // tile 0
-    issue_k(0, kbuf0, off_prev);
+    // window to land and are waited for just before the window's closing barrier.  The row offsets of tile W+2 are picked up
+    // from the ring in window W (so that the LDS read is not waited for), and tile W+RING_AHEAD's are formed by wavefront W%8.
+    // ---- prologue: offsets of tiles 0..RING_AHEAD, K tile 0
+    produce(wave);
+    if (wave == 0) produce(RING_AHEAD);
+    __syncthreads();
+    RowOffs off_v = read_offs(0);  // offsets of the tile whose V is fetched next
+    issue_k(kbuf0, off_v);
+    RowOffs off_k = read_offs(1);  // offsets of the tile whose K is fetched next (rows past the end repeat the last row)
     tile_landed();
     __syncthreads();
 
     // ---- window 0: QK(0), then step 0 without PV
     {
-        const RowOffs off_new = offs_next();  // tile 1 (clamped to the last row if it does not exist)
-        issue_k(1, kbuf1, off_new);
-        issue_v(vbuf0, off_prev);
-        off_prev = off_new;
+        issue_k(kbuf1, off_k);
+        issue_v(vbuf0, off_v);
+        off_v = off_k;
+        off_k = read_offs(2);
         qk(kbuf0, 0, sreg[0]);
         step(T_{}, F_{}, T_{}, P0{}, 0u, kbuf0, vbuf0);
         tile_landed();
@@ -559,14 +535,16 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         char* const kb_fill = WPAR ? kbuf0 : kbuf1;      // K tile Wn+1
         char* const vb = WPAR ? vbuf0 : vbuf1;           // V tile Wn-1
         char* const vb_fill = WPAR ? vbuf1 : vbuf0;      // V tile Wn
-        const RowOffs off_new = offs_next();             // tile Wn+1
         // K loads before the first step, V loads between the two steps: enqueueing all of them at once measured 1-3 % slower (the
         // memory pipeline backs up), spreading them further over the MFMA groups slower still (each issue stalls the wavefront)
-        issue_k(Wn + 1u, kb_fill, off_new);
+        issue_k(kb_fill, off_k);
+        const RowOffs off_ahead = read_offs(Wn + 2u);
+        if (wave == (Wn & (uint32_t)(NW - 1))) produce(Wn + RING_AHEAD);
         step_manual(P1{}, kb, vb, 2 * Wn - 1);
-        issue_v(vb_fill, off_prev);
+        issue_v(vb_fill, off_v);
         step_manual(P0{}, kb, vb, 2 * Wn);
-        off_prev = off_new;
+        off_v = off_k;
+        off_k = off_ahead;
         tile_landed();
         __syncthreads();
     };
@@ -583,7 +561,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     if (W < n_tiles) {
         const char* kb = (W & 1u) ? kbuf1 : kbuf0;
         const char* vb = (W & 1u) ? vbuf0 : vbuf1;
-        issue_v((W & 1u) ? vbuf1 : vbuf0, off_prev);  // V tile W, the last one
+        issue_v((W & 1u) ? vbuf1 : vbuf0, off_v);  // V tile W, the last one
         step(T_{}, T_{}, T_{}, P1{}, 2 * W - 1, kb, vb);
         step(T_{}, T_{}, T_{}, P0{}, 2 * W, kb, vb);
         tile_landed();
@@ -629,7 +607,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     }
 }
 
-template <int D, int QT, bool GROUP, bool PAD>
+template <int D, int QT, bool PAD>
 static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
@@ -637,20 +615,14 @@ static hipError_t launch_t(const AttnArgs& a, hipStream_t stream) {
     const uint64_t total = (uint64_t)n_units * q_tiles;
     if (total > 0x7ffffff0ull) return hipErrorInvalidConfiguration;
     const uint32_t per_xcd = (uint32_t)((total + 7u) / 8u);
-    attn_fwd_bf16_kernel<D, QT, GROUP, PAD><<<8u * per_xcd, NTHREADS, 0, stream>>>(a, q_tiles, (uint32_t)total, per_xcd);
+    attn_fwd_bf16_kernel<D, QT, PAD><<<8u * per_xcd, NTHREADS, 0, stream>>>(a, q_tiles, (uint32_t)total, per_xcd);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
-    const bool group = a.g.b != 0;
-    if (a.head_dim == 128) {
-        if (a.pad) return group ? launch_t<128, ATTN_QT, true, true>(a, stream) : launch_t<128, ATTN_QT, false, true>(a, stream);
-        return group ? launch_t<128, ATTN_QT, true, false>(a, stream) : launch_t<128, ATTN_QT, false, false>(a, stream);
-    }
-    if (a.head_dim == 64) {
-        if (a.pad) return group ? launch_t<64, ATTN_QT, true, true>(a, stream) : launch_t<64, ATTN_QT, false, true>(a, stream);
-        return group ? launch_t<64, ATTN_QT, true, false>(a, stream) : launch_t<64, ATTN_QT, false, false>(a, stream);
-    }
+    // one kernel serves the token-wise, group-wise and dense index maps: the map is only evaluated when the offset ring is filled
+    if (a.head_dim == 128) return a.pad ? launch_t<128, ATTN_QT, true>(a, stream) : launch_t<128, ATTN_QT, false>(a, stream);
+    if (a.head_dim == 64) return a.pad ? launch_t<64, ATTN_QT, true>(a, stream) : launch_t<64, ATTN_QT, false>(a, stream);
     return hipErrorInvalidValue;
 }
 
