@@ -228,12 +228,15 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
         const char* t1 = PARITY ? s1buf1 : s1buf0;
         const char* t2 = PARITY ? s2buf1 : s2buf0;
         const bool more = t + 1 < n_t;
-        if (more) issue_tile(t + 1, off_next, PARITY ? s1buf0 : s1buf1, PARITY ? s2buf0 : s2buf1);
+        const RowOffs off_now = off_next;
         off_next = read_offs(t + 2u);  // picked up a tile early so that the LDS read is not waited for
         if (wave == (t & (uint32_t)(BNW - 1))) produce(t + BRING_AHEAD);
         const bool tail = MODE == BWD_DQ && !PAD && !more && (n_seq % BT) != 0;  // dQ: streamed keys past the end are masked
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {
+            // The next tile's loads are enqueued halfway through this one on purpose: with a whole tile of slack even L2 misses are
+            // hidden, the workgroups that walk the same unit drift apart and stop sharing its tiles through the L2.
+            if (blk == 1 && more) issue_tile(t + 1, off_now, PARITY ? s1buf0 : s1buf1, PARITY ? s2buf0 : s2buf1);
             f32x16 m1, m2;
 #pragma unroll
             for (int r = 0; r < 16; r++) {

@@ -503,9 +503,9 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
 
     const uint32_t n_tiles = (n_seq + KT - 1) / KT;
 
-    // Staging schedule.  Window W reads K tile W and V tile W-1 from LDS.  At its start it enqueues the direct loads of K tile
-    // W+1 (into the K buffer that window W-1 read) and of V tile W (into the V buffer that window W-1 read); they have the whole
-    // window to land and are waited for just before the window's closing barrier.  The row offsets of tile W+2 are picked up
+    // Staging schedule.  Window W reads K tile W and V tile W-1 from LDS.  Between its two steps it enqueues the direct loads of
+    // K tile W+1 (into the K buffer that window W-1 read) and of V tile W (into the V buffer that window W-1 read); they have half
+    // a window to land and are waited for just before the window's closing barrier.  The row offsets of tile W+2 are picked up
     // from the ring in window W (so that the LDS read is not waited for), and tile W+RING_AHEAD's are formed by wavefront W%8.
     // ---- prologue: offsets of tiles 0..RING_AHEAD, K tile 0
     produce(wave);
@@ -535,12 +535,16 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         char* const kb_fill = WPAR ? kbuf0 : kbuf1;      // K tile Wn+1
         char* const vb = WPAR ? vbuf0 : vbuf1;           // V tile Wn-1
         char* const vb_fill = WPAR ? vbuf1 : vbuf0;      // V tile Wn
-        // K loads before the first step, V loads between the two steps: enqueueing all of them at once measured 1-3 % slower (the
-        // memory pipeline backs up), spreading them further over the MFMA groups slower still (each issue stalls the wavefront)
-        issue_k(kb_fill, off_k);
+        // The next tiles' loads are enqueued between the two steps, i.e. with HALF a window of slack, on purpose.  The workgroups
+        // of an XCD that walk the same unit share its K/V tiles through the L2 only while they stay close together, and what keeps
+        // them together is that the one in front, which misses the L2, waits for its data while the others, which hit, catch up.
+        // With a whole window of slack (loads at the window's start) even the misses are hidden, the workgroups drift apart and
+        // the L2 misses quadruple (measured: 2.4e8 instead of 5.7e7 per call, and 1.6 % more time); spreading the issues over the
+        // MFMA groups is slower still (each issue stalls the wavefront).
         const RowOffs off_ahead = read_offs(Wn + 2u);
         if (wave == (Wn & (uint32_t)(NW - 1))) produce(Wn + RING_AHEAD);
         step_manual(P1{}, kb, vb, 2 * Wn - 1);
+        issue_k(kb_fill, off_k);
         issue_v(vb_fill, off_v);
         step_manual(P0{}, kb, vb, 2 * Wn);
         off_v = off_k;

@@ -15,6 +15,8 @@
 //     which is the order ds_read_b64_tr_b8 (transposing LDS read for bytes) delivers V^T in.
 //   * K rows are padded to D+16 bytes and V rows to D+32 bytes in LDS so that the 16-byte fragment reads and the
 //     transposing reads spread over the banks.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace skiparse {
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     const uint32_t st_row = (tid / TPR) % KT8, st_piece = tid % TPR;
     const bool st_active = tid < KT8 * TPR;  // with short rows only part of the workgroup stages
     u32x4 kreg[CPT], vreg[CPT];
-    auto load_tile = [&](uint32_t t) {
+    auto load_tile = [&](uint32_t t) __attribute__((always_inline)) {
         uint32_t j = t * KT8 + st_row;
         j = j < n_seq ? j : n_seq - 1u;
         const size_t off = (size_t)j * C + (st_piece * CPT) * 16;
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
             vreg[i] = *(const u32x4*)(Vg + off + i * 16);
         }
     };
-    auto store_tile = [&](uint32_t buf) {
+    auto store_tile = [&](uint32_t buf) __attribute__((always_inline)) {
         if (!st_active) return;
 #pragma unroll
         for (int i = 0; i < CPT; i++) {
@@ -141,8 +143,11 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     __syncthreads();
 
     float sk_cur = skp[0], sv_cur = svp[0], sk_nxt, sv_nxt;
-    for (uint32_t t = 0; t < n_kt; t++) {
-        const bool more = t + 1 < n_kt;
+    // one key tile; LAST (compile time) marks the final tile, the only one that may hold keys past the end: the masking code must
+    // not be in the other tiles' path at all (the compiler turns a run-time test into 32 compares and selects per tile)
+    auto tile_body = [&](auto LASTC, uint32_t t) __attribute__((always_inline)) {
+        constexpr bool LAST = decltype(LASTC)::value;
+        const bool more = !LAST;
         if (more) load_tile(t + 1);
         const char* kb = lds_k + (t & 1u) * K_BYTES;
         const char* vb = lds_v + (t & 1u) * V_BYTES;
@@ -167,7 +172,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
                 sacc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[j], sacc[kt], 0, 0, 0, 0, 0, 0);
             }
         }
-        if (!more && (n_seq % KT8) != 0) {
+        if (LAST && (n_seq % KT8) != 0) {
 #pragma unroll
             for (int kt = 0; kt < 2; kt++)
 #pragma unroll
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
         // wavefront takes the rare path: true maximum, reference raised, tile redone.
         const float lg = __builtin_amdgcn_logf(pg);   // log2 of the gain of this key block
         const float inv_pg = __builtin_amdgcn_rcpf(pg);
-        auto probs = [&](float mref_eff, i32x8& dst) -> float {
+        auto probs = [&](float mref_eff, i32x8& dst) __attribute__((always_inline)) -> float {
             float lsum = 0.f;
 #pragma unroll
             for (int kt = 0; kt < 2; kt++) {
@@ -251,7 +256,9 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
         sk_cur = sk_nxt;
         sv_cur = sv_nxt;
         __syncthreads();
-    }
+    };
+    for (uint32_t t = 0; t + 1 < n_kt; t++) tile_body(std::false_type{}, t);
+    tile_body(std::true_type{}, n_kt - 1u);
 
     // epilogue: O = O^T * sv_max / gain / l, bf16, scattered to the original layout
     float llo, lhi;
