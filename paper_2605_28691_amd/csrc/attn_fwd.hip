@@ -65,7 +65,7 @@ constexpr int ATTN_QT = 1;       // 32-query tiles per wavefront
 constexpr int RING_AHEAD = NW;   // row offsets are formed this many tiles ahead, by one wavefront per window in turn
 constexpr int RING = 16;         // tiles of row offsets (and key validity) kept in LDS: a slot is rewritten RING - RING_AHEAD windows after its last use
 static_assert((NW & (NW - 1)) == 0 && (RING & (RING - 1)) == 0 && RING >= RING_AHEAD + 4, "ring sizes");
-constexpr int LDS_AHEAD = 3;     // MFMA groups by which the LDS fragment reads run ahead in the steady state
+constexpr int LDS_AHEAD = 4;     // MFMA groups by which the LDS fragment reads run ahead in the steady state
 constexpr float RESCALE_LOG2 = 8.0f;  // the reference maximum is only raised when it grew by more than 2^8
 
 template <int D>
