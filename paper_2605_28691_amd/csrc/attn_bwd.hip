@@ -4,19 +4,20 @@
 //     delta_i = sum_d dO_id O_id                      (= sum_j P_ij dP_ij; one small kernel)
 //     dP = dO V^T,  dS = P o (dP - delta 1^T)
 //     dQ = scale dS K,   dK = scale dS^T Q,   dV = P^T dO
-// Three launches of one kernel template, each the forward kernel's scheme with the roles of the tensors exchanged: a lane
-// OWNS one row (a query for dQ, a key for dK and dV) whose operands stay in registers for the whole walk, and the rows of the
-// other side are STREAMED through LDS in tiles of 64:
-//     M1^T[streamed, owner] = A1 B1^T      (dQ: K Q^T;     dK, dV: Q K^T)        A1 from LDS, B1 = owner registers
-//     M2^T[streamed, owner] = A2 B2^T      (dQ: V dO^T;    dK: dO V^T;  dV: none)
-//     R = elementwise(M1, M2)              (dQ, dK: dS;    dV: P)                 registers, rounded to bf16
+// Two launches of one kernel template, each the forward kernel's scheme with the roles of the tensors exchanged: a lane OWNS
+// one row (a query in the dQ launch, a key in the dK+dV launch) and the rows of the other side are STREAMED through LDS in
+// tiles of 64:
+//     M1^T[streamed, owner] = A1 B1^T      (dQ: K Q^T;     dK+dV: Q K^T)         A1 from LDS, B1 = owner (registers)
+//     M2^T[streamed, owner] = A2 B2^T      (dQ: V dO^T;    dK+dV: dO V^T)        A2 from LDS, B2 = owner (dQ: registers, dK+dV: LDS)
+//     R = elementwise(M1, M2)              (dS; in the dK+dV launch also P)       registers, rounded to bf16
 //     acc^T[channel, owner] += A3^T R      (dQ: K^T dS^T;  dK: Q^T dS;  dV: dO^T P)   A3 read from LDS with the transposing read
 // As in the forward kernel the 32x32 accumulator layout gives every lane one owner column, so R's registers are directly the
-// B operand of the last product, and the owner's gradient row is accumulated in registers and written once: no atomics, the
-// result is deterministic.  dK and dV are separate launches because their accumulators together (128 registers) would not
-// leave room for two wavefronts per SIMD; the price is that S is recomputed once more (8 matrix products instead of 7).
-//   * log-sum-exp and delta are per QUERY: per-lane constants in the dQ launch, per-streamed-row values (staged in LDS next
-//     to the tile, +inf / 0 past the end so that such rows contribute nothing) in the other two.
+// B operand of the last product, and the owner's gradient rows are accumulated in registers and written once: no atomics, the
+// result is deterministic.  dK and dV share one launch (S and dP are formed once for both: 7 matrix products in all against the
+// 5 of the definition); their two accumulators take 128 registers at head_dim 128, so the owner's V rows are kept in LDS there.
+//   * log-sum-exp and delta are per QUERY: per-lane constants in the dQ launch; in the dK+dV launch per-streamed-row values,
+//     staged in LDS next to the tile as -L/scale and -delta and used as the INITIAL accumulators of M1 and M2, so that
+//     P = exp2(M1 * c) and dS = P o M2 need no further arithmetic (-inf / 0 for rows that must contribute nothing).
 //   * Streamed tiles go from global memory straight into LDS (global_load_lds_dwordx4), rows packed, chunk positions XOR-swizzled
 //     with the row number so that a tile serves both the 16-byte fragment reads and ds_read_b64_tr_b16 without bank conflicts.
 //   * Rows are addressed through the Skiparse index map (Algorithm 1) exactly as in the forward kernel, so q, k, v, dO and the
@@ -47,7 +48,7 @@ constexpr int BRING = 16;          // tiles of row offsets kept in LDS
 static_assert((BNW & (BNW - 1)) == 0 && (BRING & (BRING - 1)) == 0 && BRING >= BRING_AHEAD + 4, "ring sizes");
 
 // PAD: any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s; a padding position is skipped as an
-// owner and contributes nothing as a streamed row (a -inf logit bias in the dQ launch, a +inf log-sum-exp in the other two).
+// owner and contributes nothing as a streamed row (a -inf bias as the initial accumulator of the logits in both launches).
 template <int D, int MODE, bool PAD>
 __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_tiles, uint32_t total, uint32_t per_xcd) {
     constexpr int KS = D / 16;   // MFMA steps along head_dim
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     constexpr int RB = D * 2;    // row bytes in LDS (packed rows, swizzled chunk positions)
     constexpr int RPI = 64 / CH; // rows filled by one direct-to-LDS instruction of a wavefront
     constexpr int IPW = CH / BNW;  // such instructions per wavefront, tensor and tile
-    constexpr bool TWO = MODE != BWD_DV; // second product M2 present
+    constexpr bool DKV = MODE == BWD_DKV; // dK and dV together: two accumulators, the owner's second operand (V) lives in LDS
     constexpr int TILE_BYTES = BT * RB;
     static_assert(IPW >= 1 && IPW * BNW == CH, "a tile is CH instructions, spread evenly over the wavefronts");
     // two streamed tensors, double buffered; separate arrays so that the compiler can tell the tile being filled from the one
@@ -65,8 +66,9 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     __shared__ __attribute__((aligned(1024))) char s1buf1[TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char s2buf0[TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char s2buf1[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) float row_l[2][BT];  // dK, dV: log2-domain log-sum-exp of the streamed queries
-    __shared__ __attribute__((aligned(16))) float row_d[2][BT];  // dK: their delta
+    __shared__ __attribute__((aligned(1024))) char own2buf[DKV ? 32 * BNW * RB : 16];  // DKV: V rows of the 256 owners, swizzled like a tile
+    __shared__ __attribute__((aligned(16))) float row_l[2][BT];  // initial M1 per streamed row: dK+dV -L/scale of the query; dQ (PAD) 0 / -inf
+    __shared__ __attribute__((aligned(16))) float row_d[2][BT];  // initial M2 per streamed row: dK+dV -delta of the query
     __shared__ __attribute__((aligned(16))) uint32_t rowoff[BRING][BT];     // byte offsets of the streamed rows of the next tiles
     __shared__ __attribute__((aligned(16))) unsigned char rowok[BRING][BT]; // PAD only: 1 = the row is a real token
 
@@ -95,7 +97,8 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     const __bf16* own2_g = (const __bf16*)(MODE == BWD_DQ ? a.dout : a.v) + unit_off;
     const char* st1_g = (const char*)((const __bf16*)(MODE == BWD_DQ ? a.k : a.q) + unit_off);
     const char* st2_g = (const char*)((const __bf16*)(MODE == BWD_DQ ? a.v : a.dout) + unit_off);
-    __bf16* grad_g = (__bf16*)(MODE == BWD_DQ ? a.dq : MODE == BWD_DK ? a.dk : a.dv) + unit_off;
+    __bf16* grad_g = (__bf16*)(MODE == BWD_DQ ? a.dq : a.dk) + unit_off;
+    __bf16* grad2_g = (__bf16*)a.dv + unit_off;  // DKV: the second gradient
 
     // ---- owner row: operands in registers (B operands: lane = owner lq, 8 consecutive channels starting at 16*ks + 8*h)
     const uint32_t jo = ot * (32u * BNW) + wave * 32u + lq;
@@ -110,11 +113,11 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     const uint32_t own_tok = token_at(jo_c, &own_real);
     const bool own_valid = jo < n_seq && own_real;
     const size_t own_off = (size_t)(own_real ? own_tok : 0u) * C;  // a padding owner reads token 0 and stores nothing
-    bf16x8 own1[KS], own2[TWO ? KS : 1];
+    bf16x8 own1[KS], own2[DKV ? 1 : KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
         own1[ks] = *(const bf16x8*)(own1_g + own_off + ks * 16 + 8 * h);
-        if (TWO) own2[ks] = *(const bf16x8*)(own2_g + own_off + ks * 16 + 8 * h);
+        if (!DKV) own2[ks] = *(const bf16x8*)(own2_g + own_off + ks * 16 + 8 * h);
     }
     float own_l = 0.f, own_d = 0.f;  // dQ: the owner is a query
     if (MODE == BWD_DQ) {
@@ -122,6 +125,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
         own_d = delta_u[jo_c];
     }
     const float c = a.scale * LOG2E;  // exp(x*scale - L) = exp2(x*c - L*log2e)
+    const float inv_scale = 1.0f / a.scale;
 
     // ---- staging of streamed tiles: global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at the
     // instruction's LDS base + 16*l, one instruction fills RPI rows).  Chunk c of row r is stored at chunk position c ^ swz(r),
@@ -163,35 +167,40 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(st2_g + o.off[i]),
                                              (LDS_PTR(void))(b2 + (wave * IPW + i) * 1024u), 16, 0, 0);
         }
-        if ((MODE != BWD_DQ || PAD) && tid < BT) {  // per-row values of the streamed rows; rows past the end contribute nothing
+        if ((DKV || PAD) && tid < BT) {  // per-row values of the streamed rows; rows past the end contribute nothing
             const uint32_t jj = t * BT + tid;
             const bool ok = jj < n_seq && (!PAD || rowok[t % BRING][tid] != 0);
+            // The values are the INITIAL accumulators of the two products, so that they cost no arithmetic of their own:
             if (MODE == BWD_DQ) {
-                rl = ok ? 0.f : -INFINITY;  // streamed keys: a logit bias
+                rl = ok ? 0.f : -INFINITY;  // streamed keys: a bias on the raw logit
             } else {
-                rl = ok ? lse_u[jj] * LOG2E : INFINITY;  // streamed queries: P = exp2(s*c - L) = 0 for L = +inf
-                rd = (MODE == BWD_DK && ok) ? delta_u[jj] : 0.f;
+                // streamed queries: raw logit - L/scale, times c = s*c - L*log2e; -inf for a row that contributes nothing (P = 0)
+                rl = ok ? -lse_u[jj] * inv_scale : -INFINITY;
+                rd = ok ? -delta_u[jj] : 0.f;  // dP - delta
             }
         }
     };
     auto store_rowvals = [&](uint32_t buf) __attribute__((always_inline)) {
-        if ((MODE != BWD_DQ || PAD) && tid < BT) {
+        if ((DKV || PAD) && tid < BT) {
             row_l[buf][tid] = rl;
             row_d[buf][tid] = rd;
         }
     };
     auto tile_landed = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
-    f32x16 acc[MT];
+    f32x16 acc[MT], acc2[DKV ? MT : 1];  // acc2: dV in the DKV launch
 #pragma unroll
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) acc[mt][r] = 0.f;
+        for (int r = 0; r < 16; r++) {
+            acc[mt][r] = 0.f;
+            if (DKV) acc2[mt][r] = 0.f;
+        }
 
     // fragment of MFMA step ks: row lq (+ 32*blk), chunk 2*ks + h at its swizzled position.  The position of step ks is that of
     // step 0 with ks*32 XORed in (the row part lies above the chunk bits), so one register and an XOR per read can replace the
-    // table; the dK launch, the tightest on registers, does that.
-    constexpr bool ADDR_TABLE = MODE != BWD_DK;
+    // table; the dK+dV launch, the tightest on registers, does that.
+    constexpr bool ADDR_TABLE = !DKV;
     const uint32_t a_rd0 = lq * RB + ((h ^ swz(lq)) * 16u);
     uint32_t a_rd_tab[ADDR_TABLE ? KS : 1];
     if (ADDR_TABLE) {
@@ -212,6 +221,21 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
         }
 
     const uint32_t n_t = (n_seq + BT - 1) / BT;
+    if (DKV) {
+        // the wavefront's 32 owner rows of V go straight into LDS (one instruction fills RPI rows; same swizzle as the tiles, so
+        // the fragment of MFMA step ks sits at a_rd(ks) of the wavefront's 32-row block); waited for with tile 0
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; i++) {
+            const uint32_t r = (uint32_t)i * RPI + lane / CH;  // row of the wavefront's block
+            const uint32_t j = ot * (32u * BNW) + wave * 32u + r;
+            bool real;
+            const uint32_t tok = token_at(j < n_seq ? j : n_seq - 1u, &real);
+            const uint32_t off = (real ? tok : 0u) * row_bytes + (((lane % CH) ^ swz(r)) * 16u);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)own2_g + off),
+                                             (LDS_PTR(void))(own2buf + wave * 32u * RB + (uint32_t)i * 1024u), 16, 0, 0);
+        }
+    }
+    const char* const own2_lds = own2buf + (DKV ? wave * 32u * RB : 0u);
     produce(wave);  // tiles 0 .. BRING_AHEAD-1
     __syncthreads();
     issue_tile(0, read_offs(0), s1buf0, s2buf0);
@@ -237,67 +261,76 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             // The next tile's loads are enqueued halfway through this one on purpose: with a whole tile of slack even L2 misses are
             // hidden, the workgroups that walk the same unit drift apart and stop sharing its tiles through the L2.
             if (blk == 1 && more) issue_tile(t + 1, off_now, PARITY ? s1buf0 : s1buf1, PARITY ? s2buf0 : s2buf1);
+            // register r of a block is streamed row 8*(r/4) + 4*h + r%4; the per-row values start the accumulators
             f32x16 m1, m2;
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                m1[r] = 0.f;
-                m2[r] = 0.f;
+            for (int g = 0; g < 4; g++) {
+                f32x4 i1 = {0.f, 0.f, 0.f, 0.f}, i2 = {0.f, 0.f, 0.f, 0.f};
+                if (DKV || PAD) i1 = *(const f32x4*)&row_l[PARITY][blk * 32 + 8 * g + 4 * h];
+                if (DKV) i2 = *(const f32x4*)&row_d[PARITY][blk * 32 + 8 * g + 4 * h];
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    m1[4 * g + e] = i1[e];
+                    m2[4 * g + e] = i2[e];
+                }
             }
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) {
                 const bf16x8 f1 = *(const bf16x8*)(t1 + a_rd(ks) + blk * 32 * RB);
                 m1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, own1[ks], m1, 0, 0, 0);
             }
-            if (TWO) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ks++) {
-                    const bf16x8 f2 = *(const bf16x8*)(t2 + a_rd(ks) + blk * 32 * RB);
-                    m2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, own2[ks], m2, 0, 0, 0);
-                }
+            for (int ks = 0; ks < KS; ks++) {
+                const bf16x8 f2 = *(const bf16x8*)(t2 + a_rd(ks) + blk * 32 * RB);
+                const bf16x8 o2 = DKV ? *(const bf16x8*)(own2_lds + a_rd(ks)) : own2[DKV ? 0 : ks];
+                m2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, o2, m2, 0, 0, 0);
             }
-            // register r of a block is streamed row 8*(r/4) + 4*h + r%4
-            f32x4 sl[4], sd[4];
-            if (MODE != BWD_DQ || PAD) {
-#pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    sl[g] = *(const f32x4*)&row_l[PARITY][blk * 32 + 8 * g + 4 * h];
-                    if (MODE == BWD_DK) sd[g] = *(const f32x4*)&row_d[PARITY][blk * 32 + 8 * g + 4 * h];
-                }
-            }
-            bf16x8 rf[2];
+            bf16x8 rf[2], rp[DKV ? 2 : 1];  // rp: P itself in the DKV launch (rf holds dS there)
 #pragma unroll
             for (int g2 = 0; g2 < 2; g2++) {
-                bf16x8 pk;
+                bf16x8 pk, pp;
 #pragma unroll
                 for (int e = 0; e < 8; e += 2) {
-                    f32x2 val;
+                    f32x2 val, prob;
 #pragma unroll
                     for (int u = 0; u < 2; u++) {
                         const int r = g2 * 8 + e + u;
-                        const float l2 = MODE != BWD_DQ ? sl[r >> 2][r & 3] : PAD ? own_l - sl[r >> 2][r & 3] : own_l;
-                        float pr = __builtin_amdgcn_exp2f(fmaf(m1[r], c, -l2));
+                        float pr = MODE == BWD_DQ ? __builtin_amdgcn_exp2f(fmaf(m1[r], c, -own_l)) : __builtin_amdgcn_exp2f(m1[r] * c);
                         if (tail) {
                             const uint32_t row = t * BT + blk * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
                             pr = row < n_seq ? pr : 0.f;
                         }
-                        if (MODE == BWD_DV) val[u] = pr;
-                        else val[u] = pr * (m2[r] - (MODE == BWD_DQ ? own_d : sd[r >> 2][r & 3]));
+                        val[u] = MODE == BWD_DQ ? pr * (m2[r] - own_d) : pr * m2[r];
+                        prob[u] = pr;
                     }
                     const bf16x2 vb = __builtin_convertvector(val, bf16x2);
                     pk[e] = vb[0];
                     pk[e + 1] = vb[1];
+                    if (DKV) {
+                        const bf16x2 pb = __builtin_convertvector(prob, bf16x2);
+                        pp[e] = pb[0];
+                        pp[e + 1] = pb[1];
+                    }
                 }
                 rf[g2] = pk;
+                if (DKV) rp[g2] = pp;
             }
 #pragma unroll
             for (int g2 = 0; g2 < 2; g2++)
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++) {
-                    const char* ta = (MODE == BWD_DV ? t2 : t1) + (blk * 32 + g2 * 16) * RB;  // A3: dO for dV, else the first tensor
+                    const char* ta = t1 + (blk * 32 + g2 * 16) * RB;  // A3 of dQ and dK: the first streamed tensor
                     const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[0][mt]));
                     const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[1][mt]));
                     const bf16x8 tf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
                     acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, rf[g2], acc[mt], 0, 0, 0);
+                    if (DKV) {  // dV^T += dO^T P with the dO tile
+                        const char* tb = t2 + (blk * 32 + g2 * 16) * RB;
+                        const bf16x4 w0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(tb + t_rd[0][mt]));
+                        const bf16x4 w1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(tb + t_rd[1][mt]));
+                        const bf16x8 tg = __builtin_shufflevector(w0, w1, 0, 1, 2, 3, 4, 5, 6, 7);
+                        acc2[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tg, rp[g2], acc2[mt], 0, 0, 0);
+                    }
                 }
         }
         if (more) store_rowvals(PARITY ^ 1);
@@ -313,7 +346,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 
     // ---- epilogue: lane owns row jo; register r of block mt is channel 32*mt + 8*(r/4) + 4*h + r%4
     if (own_valid) {
-        const float f = MODE == BWD_DV ? 1.0f : a.scale;
+        const float f = a.scale;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
 #pragma unroll
@@ -322,6 +355,11 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 #pragma unroll
                 for (int e = 0; e < 4; e++) o[e] = (__bf16)(acc[mt][g * 4 + e] * f);
                 *(bf16x4*)(grad_g + own_off + mt * 32 + g * 8 + 4 * h) = o;
+                if (DKV) {
+#pragma unroll
+                    for (int e = 0; e < 4; e++) o[e] = (__bf16)acc2[mt][g * 4 + e];
+                    *(bf16x4*)(grad2_g + own_off + mt * 32 + g * 8 + 4 * h) = o;
+                }
             }
     }
 }
@@ -384,8 +422,7 @@ static hipError_t launch_all(const BwdArgs& a, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if ((e = launch_mode<D, BWD_DQ, PAD>(a, stream)) != hipSuccess) return e;
-    if ((e = launch_mode<D, BWD_DK, PAD>(a, stream)) != hipSuccess) return e;
-    return launch_mode<D, BWD_DV, PAD>(a, stream);
+    return launch_mode<D, BWD_DKV, PAD>(a, stream);
 }
 
 hipError_t launch_attn_bwd_bf16(const BwdArgs& a, hipStream_t stream) {

@@ -43,7 +43,7 @@ enum OutKind : int { OUT_AS_INPUT = 0, OUT_ORIGINAL = 1, OUT_OTHER_PATTERN = 2 }
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
 
 // Flash-attention backward, bf16: delta = rowsum(dO o O), then dQ, dK and dV (one launch each).  Addressing as in AttnArgs.
-enum BwdMode : int { BWD_DQ = 0, BWD_DV = 1, BWD_DK = 2 };
+enum BwdMode : int { BWD_DQ = 0, BWD_DKV = 1 };  // dQ (owner = query), dK and dV together (owner = key)
 struct BwdArgs {
     const void* q;
     const void* k;
