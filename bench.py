@@ -219,7 +219,7 @@ def main() -> int:
         extras["chain_token_to_group_tflops"] = round(flops / c_ms / 1e9, 2)
         del qs, ks, vs, os_
     if "bwd" in sections:
-        # training step of the layer: forward that keeps the log-sum-exp, then dQ, dK, dV (delta + three launches)
+        # training step of the layer: forward that keeps the log-sum-exp, then dQ, dK, dV (delta + two launches)
         dout = si.make_dout(w).cuda()
         lse = torch.empty((s * s * w.B, w.heads, w.Nsub), dtype=torch.float32, device="cuda")
         grads = [torch.empty_like(qd) for _ in range(3)]
@@ -230,7 +230,7 @@ def main() -> int:
         extras["fwd_lse_ms"] = round(fl_ms, 4)
         extras["bwd_ms"] = round(b_ms, 4)
         extras["bwd_effective_tflops"] = round(2.5 * flops / b_ms / 1e9, 2)  # five matrix products of the definition (forward has two)
-        extras["bwd_executed_tflops"] = round(4.0 * flops / b_ms / 1e9, 2)   # eight are executed (S is recomputed in each launch)
+        extras["bwd_executed_tflops"] = round(3.5 * flops / b_ms / 1e9, 2)   # seven are executed (S and dP are formed in both launches)
         del dout, lse, grads, wsb
     if "dense" in sections:
         d_ms = time_calls(lambda: sk.dense_attn_fwd(qd, kd, vd, T, H, W, scale=w.scale, out=out), 3, 1)

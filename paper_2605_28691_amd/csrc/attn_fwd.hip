@@ -104,7 +104,7 @@ __device__ inline size_t uniform(size_t x) {
 }
 
 // PAD selects the any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s, padding positions
-// are masked as keys (a validity byte and a 0 / -inf logit bias per staged row in LDS) and skipped as queries.
+// are masked as keys (a 0 / -inf logit bias per staged row in LDS, from which the logits' accumulators start) and skipped as queries.
 // Row of `out` for position j of subsequence sb of the input's sparse layout: the token's row in the original layout, or its
 // row in the sparse layout of the other pattern (Alg. 1: tsa_to_orig / gsa_to_orig, tsa_to_gsa / gsa_to_tsa).
 __device__ inline size_t scattered_row(const AttnArgs& a, uint32_t sb, uint32_t j) {
@@ -141,8 +141,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     __shared__ __attribute__((aligned(1024))) char vbuf0[TL::TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char vbuf1[TL::TILE_BYTES];
     __shared__ __attribute__((aligned(16))) uint32_t rowoff[RING][KT];        // byte offsets of the rows of the next tiles
-    __shared__ __attribute__((aligned(16))) unsigned char kmask[RING][KT];    // PAD only: 1 = real key, per row of a K tile
-    __shared__ __attribute__((aligned(16))) float kbias[RING][KT];            // PAD only: the same as a logit bias, 0 or -inf
+    __shared__ __attribute__((aligned(16))) float kbias[RING][KT];            // PAD only: logit bias per row of a K tile, 0 = real key, -inf = padding
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = uniform(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
@@ -207,7 +206,6 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
             const uint32_t tok = src_token_padded(a.g, p, q, jc, &real);
             const bool valid = j < n_seq && real;
             off = valid ? tok * row_bytes : 0u;  // padding rows read token 0; their logits are masked
-            kmask[tile % RING][lane] = valid ? 1 : 0;
             kbias[tile % RING][lane] = valid ? 0.f : -INFINITY;
         } else {
             off = j < n_seq ? src_token(a.g, p, q, jc) * row_bytes : last_off;
@@ -289,13 +287,24 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
             v_rd[sec][mt] = row * TL::RB + ((ch ^ TL::swz(row)) * 16u) + 8 * (li & 1u);
         }
 
-    // S(block) = K(block) Q^T from K tile buffer kb, 32-key half `half`; each K fragment feeds all QT query tiles
-    auto qk = [&](const char* kb, int half, f32x16 (&s)[QT]) __attribute__((always_inline)) {
+    // Initial accumulator of the logits of 32-key block blkq: zero, or in the any-resolution mode the keys' bias (0 / -inf), which
+    // masks the padding positions without any arithmetic of its own.  Register r of the block is key 8*(r/4) + 4*h + r%4.
+    auto s_init = [&](uint32_t blkq) __attribute__((always_inline)) -> f32x16 {
+        f32x16 v;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            f32x4 b4 = {0.f, 0.f, 0.f, 0.f};
+            if (PAD) b4 = *(const f32x4*)&kbias[(blkq >> 1) % RING][(blkq & 1u) * 32u + 8 * i + 4 * h];
+#pragma unroll
+            for (int e = 0; e < 4; e++) v[4 * i + e] = b4[e];
+        }
+        return v;
+    };
+    // S(block blkq) = K(block) Q^T from K tile buffer kb, 32-key half `half`; each K fragment feeds all QT query tiles
+    auto qk = [&](const char* kb, int half, f32x16 (&s)[QT], uint32_t blkq) __attribute__((always_inline)) {
         f32x16 acc[QT];
 #pragma unroll
-        for (int qi = 0; qi < QT; qi++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[qi][r] = 0.f;
+        for (int qi = 0; qi < QT; qi++) acc[qi] = s_init(blkq);
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
             const bf16x8 kf = *(const bf16x8*)(kb + k_rd[ks] + half * 32 * TL::RB);
@@ -348,25 +357,16 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     auto step = [&](auto DO_QK, auto DO_PV, auto MASK, auto PARC, uint32_t blk, const char* kb, const char* vb) __attribute__((always_inline)) {
         constexpr int PAR = decltype(PARC)::value;
         apply_pending();
-        if (decltype(DO_QK)::value) qk(kb, PAR ^ 1, sreg[PAR ^ 1]);
+        if (decltype(DO_QK)::value) qk(kb, PAR ^ 1, sreg[PAR ^ 1], blk + 1u);
         unsigned long long grow_mask = 0;
 #pragma unroll
         for (int qi = 0; qi < QT; qi++) {
             f32x16& s = sreg[PAR][qi];
-            if (decltype(MASK)::value) {
-                if (PAD) {
+            if (decltype(MASK)::value && !PAD) {  // PAD: positions past the end carry the -inf bias like every padding position
 #pragma unroll
-                    for (int i = 0; i < 4; i++) {  // keys 8*i + 4*h + 0..3 of the block: one dword of validity bytes
-                        const uint32_t m4 = *(const uint32_t*)&kmask[(blk >> 1) % RING][(blk & 1u) * 32u + 8 * i + 4 * h];
-#pragma unroll
-                        for (int e = 0; e < 4; e++) s[4 * i + e] = ((m4 >> (8 * e)) & 1u) ? s[4 * i + e] : -INFINITY;
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const uint32_t key = blk * 32u + 8 * (r >> 2) + 4 * h + (r & 3);
-                        s[r] = key < n_seq ? s[r] : -INFINITY;
-                    }
+                for (int r = 0; r < 16; r++) {
+                    const uint32_t key = blk * 32u + 8 * (r >> 2) + 4 * h + (r & 3);
+                    s[r] = key < n_seq ? s[r] : -INFINITY;
                 }
             }
             const float mx = fmaxf(max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8])),
@@ -394,8 +394,8 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     // wavefront takes the rare path, which finds the true maximum, redoes the block's exponentials against it and rescales
     // O and l.  Probabilities up to 2^16 are harmless: bf16 keeps their relative precision and O, l are fp32.
     // LDS fragments are read two MFMA groups ahead and every fragment feeds the MFMAs of all QT query tiles.
-    // In the any-resolution mode (PAD) the same step adds a per-key bias (0 for a real key, -inf for a padding position, staged
-    // next to the K tile) to the exponent, which costs one subtraction per key; `blk` is the block whose softmax this step does.
+    // In the any-resolution mode (PAD) the logits start from the keys' bias instead of zero (see s_init), nothing else differs;
+    // `blk` is the block whose softmax this step does (the logits it forms are those of block blk + 1).
     auto step_manual = [&](auto PARC, const char* kb, const char* vb, uint32_t blk) __attribute__((always_inline)) {
         constexpr int PAR = decltype(PARC)::value;
         constexpr int NPV = 2 * MT, NQK = KS, NG = NPV + NQK;
@@ -425,11 +425,6 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
             lsum[qi] = 0.f;
             mc[qi] = m_ref[qi] * c;
         }
-        f32x4 bias[4];  // PAD: register r of the block is key 8*(r/4) + 4*h + r%4
-        if (PAD) {
-#pragma unroll
-            for (int i = 0; i < 4; i++) bias[i] = *(const f32x4*)&kbias[(blk >> 1) % RING][(blk & 1u) * 32u + 8 * i + 4 * h];
-        }
 #pragma unroll
         for (int g = 0; g < NG; g++) {
             if (g + LDS_AHEAD < NG) fr[g + LDS_AHEAD] = read_frag(g + LDS_AHEAD);
@@ -439,10 +434,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
                 if (g % 2 == 0) {
                     oacc[qi][i % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g], preg[PAR ^ 1][qi][i / MT], oacc[qi][i % MT], 0, 0, 0);
                 } else {
-                    if (i == 0) {
-#pragma unroll
-                        for (int r = 0; r < 16; r++) acc[qi][r] = 0.f;
-                    }
+                    if (i == 0) acc[qi] = s_init(blk + 1u);
                     acc[qi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g], qf[qi][i], acc[qi], 0, 0, 0);
                 }
             }
@@ -452,9 +444,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
                 const f32x16& s = sreg[PAR][qi];
 #pragma unroll
                 for (int e = 2 * (g * 8 / NG); e < 2 * ((g + 1) * 8 / NG); e += 2) {
-                    const float a0 = PAD ? bias[e >> 2][e & 3] - mc[qi] : -mc[qi];
-                    const float a1 = PAD ? bias[(e + 1) >> 2][(e + 1) & 3] - mc[qi] : -mc[qi];
-                    const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, a0)), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, a1))};
+                    const f32x2 pe = {__builtin_amdgcn_exp2f(fmaf(s[e], c, -mc[qi])), __builtin_amdgcn_exp2f(fmaf(s[e + 1], c, -mc[qi]))};
                     const bf16x2 pb = __builtin_convertvector(pe, bf16x2);
                     lsum[qi] += pe[0] + pe[1];
                     pk[qi][e / 8][e % 8] = pb[0];
@@ -476,10 +466,6 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
 #pragma unroll
             for (int qi = 0; qi < QT; qi++) {
                 f32x16& s = sreg[PAR][qi];
-                if (PAD) {  // padding keys out of the way before the maximum is taken
-#pragma unroll
-                    for (int r = 0; r < 16; r++) s[r] += bias[r >> 2][r & 3];
-                }
                 const float mx = fmaxf(max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8])),
                                        max3(max3(s[9], s[10], s[11]), max3(s[12], s[13], s[14]), s[15]));
                 float lo, hi;
@@ -523,7 +509,7 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         issue_v(vbuf0, off_v);
         off_v = off_k;
         off_k = read_offs(2);
-        qk(kbuf0, 0, sreg[0]);
+        qk(kbuf0, 0, sreg[0], 0u);
         step(T_{}, F_{}, T_{}, P0{}, 0u, kbuf0, vbuf0);
         tile_landed();
         __syncthreads();
