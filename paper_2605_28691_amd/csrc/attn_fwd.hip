@@ -396,26 +396,42 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
     // LDS fragments are read two MFMA groups ahead and every fragment feeds the MFMAs of all QT query tiles.
     // In the any-resolution mode (PAD) the logits start from the keys' bias instead of zero (see s_init), nothing else differs;
     // `blk` is the block whose softmax this step does (the logits it forms are those of block blk + 1).
-    auto step_manual = [&](auto PARC, const char* kb, const char* vb, uint32_t blk) __attribute__((always_inline)) {
+    // MFMA groups of a step alternate between the two products (PV, QK, PV, QK, ...: as many of each), so consecutive MFMAs never
+    // depend on each other: group g is PV group g/2 when g is even and QK group g/2 when g is odd.
+    constexpr int NPV = 2 * MT, NQK = KS, NG = NPV + NQK;
+    static_assert(NPV == NQK, "the two products have the same number of MFMA groups");
+    // LDS fragment of group g of the step with parity PAR (its PV and QK both work on the half PAR ^ 1 of their tiles)
+    auto read_frag = [&](auto PARC, const char* kb, const char* vb, int g) __attribute__((always_inline)) -> bf16x8 {
         constexpr int PAR = decltype(PARC)::value;
-        constexpr int NPV = 2 * MT, NQK = KS, NG = NPV + NQK;
-        // MFMA groups alternate between the two products (PV, QK, PV, QK, ...: NPV == NQK), so consecutive MFMAs never
-        // depend on each other: group g is PV group g/2 when g is even and QK group g/2 when g is odd.
-        static_assert(NPV == NQK, "the two products have the same number of MFMA groups");
-        auto read_frag = [&](int g) __attribute__((always_inline)) -> bf16x8 {
-            const int i = g / 2;
-            if (g % 2 == 0) {  // fragment of PV group i: 16-key group m2 = i / MT, channel block mt = i % MT
-                const char* va = vb + ((PAR ^ 1) * 32 + (i / MT) * 16) * TL::RB;
-                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[0][i % MT]));
-                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[1][i % MT]));
-                return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-            return *(const bf16x8*)(kb + k_rd[i] + (PAR ^ 1) * 32 * TL::RB);
-        };
+        const int i = g / 2;
+        if (g % 2 == 0) {  // fragment of PV group i: 16-key group m2 = i / MT, channel block mt = i % MT
+            const char* va = vb + ((PAR ^ 1) * 32 + (i / MT) * 16) * TL::RB;
+            const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[0][i % MT]));
+            const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(va + v_rd[1][i % MT]));
+            return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+        return *(const bf16x8*)(kb + k_rd[i] + (PAR ^ 1) * 32 * TL::RB);
+    };
+    struct Frags {
+        bf16x8 f[LDS_AHEAD];  // the first fragments of a step, read before it starts
+    };
+    auto first_frags = [&](auto PARC, const char* kb, const char* vb) __attribute__((always_inline)) -> Frags {
+        Frags p;
+#pragma unroll
+        for (int g = 0; g < LDS_AHEAD; g++) p.f[g] = read_frag(PARC, kb, vb, g);
+        return p;
+    };
+    // `pre`: the step's first LDS_AHEAD fragments, already on their way.  With NEXT the step's last groups fetch, instead of
+    // nothing, the first fragments of the FOLLOWING step on the same tiles (the other parity) into `nxt`, so that the LDS
+    // latency is exposed once per window instead of once per step.
+    auto step_manual = [&](auto PARC, auto NEXTC, const char* kb, const char* vb, uint32_t blk, const Frags& pre, Frags& nxt) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(PARC)::value;
+        constexpr bool NEXT = decltype(NEXTC)::value;
+        using PARN = std::integral_constant<int, PAR ^ 1>;
         apply_pending();
         bf16x8 fr[NG];  // every fragment has its own name; lifetimes are short, so few registers are live at a time
 #pragma unroll
-        for (int g = 0; g < LDS_AHEAD; g++) fr[g] = read_frag(g);
+        for (int g = 0; g < LDS_AHEAD; g++) fr[g] = pre.f[g];
         __builtin_amdgcn_sched_barrier(0);
         f32x16 acc[QT];
         float lsum[QT], mc[QT];
@@ -427,7 +443,8 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         }
 #pragma unroll
         for (int g = 0; g < NG; g++) {
-            if (g + LDS_AHEAD < NG) fr[g + LDS_AHEAD] = read_frag(g + LDS_AHEAD);
+            if (g + LDS_AHEAD < NG) fr[g + LDS_AHEAD] = read_frag(PARC, kb, vb, g + LDS_AHEAD);
+            else if (NEXT) nxt.f[g + LDS_AHEAD - NG] = read_frag(PARN{}, kb, vb, g + LDS_AHEAD - NG);
             const int i = g / 2;
 #pragma unroll
             for (int qi = 0; qi < QT; qi++) {
@@ -529,10 +546,12 @@ __global__ __launch_bounds__(NTHREADS, (QT == 1 && NW == 4 ? 2 : 1)) void attn_f
         // MFMA groups is slower still (each issue stalls the wavefront).
         const RowOffs off_ahead = read_offs(Wn + 2u);
         if (wave == (Wn & (uint32_t)(NW - 1))) produce(Wn + RING_AHEAD);
-        step_manual(P1{}, kb, vb, 2 * Wn - 1);
+        const Frags pre = first_frags(P1{}, kb, vb);
+        Frags mid, none;
+        step_manual(P1{}, T_{}, kb, vb, 2 * Wn - 1, pre, mid);
         issue_k(kb_fill, off_k);
         issue_v(vb_fill, off_v);
-        step_manual(P0{}, kb, vb, 2 * Wn);
+        step_manual(P0{}, F_{}, kb, vb, 2 * Wn, mid, none);
         off_v = off_k;
         off_k = off_ahead;
         tile_landed();
