@@ -355,12 +355,18 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 #pragma unroll
                 for (int e = 0; e < 4; e++) o[e] = (__bf16)(acc[mt][g * 4 + e] * f);
                 *(bf16x4*)(grad_g + own_off + mt * 32 + g * 8 + 4 * h) = o;
-                if (DKV) {
+            }
+        if (DKV) {  // the second row after the first is complete, so that the L2 sees whole lines of one row at a time
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4 o;
 #pragma unroll
                     for (int e = 0; e < 4; e++) o[e] = (__bf16)acc2[mt][g * 4 + e];
                     *(bf16x4*)(grad2_g + own_off + mt * 32 + g * 8 + 4 * h) = o;
                 }
-            }
+        }
     }
 }
 
