@@ -75,8 +75,6 @@ GridMap make_dense_gridmap(size_t n) {
     g.b = 0;
     g.cmul = 0;
     g.ws = make_fastdiv(0xffffffffu);  // multiplier 2: the quotient is 0 for every position below 2^31
-    g.step_r = 0;
-    g.step_w = 64;
     g.H_real = 1;
     g.hpad = make_fastdiv(1);
     g.sdiv = make_fastdiv(1);
@@ -99,8 +97,6 @@ GridMap make_gridmap(int T, int H, int W, int s, int pattern, bool pad = false) 
     g.cmul = pattern == SKIPARSE_TOKEN ? 1u : (uint32_t)s;
     g.ws = make_fastdiv((uint32_t)(Wp / s));
     g.sdiv = make_fastdiv((uint32_t)s);
-    g.step_r = 64u / (uint32_t)(Wp / s);
-    g.step_w = 64u % (uint32_t)(Wp / s);
     g.H_real = H;
     g.hpad = make_fastdiv((uint32_t)Hp);
     return g;
@@ -128,9 +124,8 @@ int permute_common(const void* src, void* dst, int B, int heads, int T, int H, i
     return finish(launch_permute(src, dst, B, g, row_bytes, to_sparse, (hipStream_t)stream));
 }
 
-// The attention kernels address rows with 32-bit byte offsets inside one batch element and form them with 24-bit
-// multiplies: tokens per batch element, row length W and bytes per token row must stay below 2^24, and one batch
-// element below 4 GiB.
+// The attention kernels address rows with 32-bit byte offsets inside one batch element: one batch element must stay below
+// 4 GiB (tokens per batch element, row length W and bytes per token row are kept below 2^24 as well).
 int check_attn_ranges(const Shape& sh, int W, int elem_bytes) {
     const uint64_t row_bytes = (uint64_t)sh.row_elems * (uint64_t)elem_bytes;
     if (sh.n_tok >= (1u << 24) || (uint64_t)W >= (1u << 24) || row_bytes >= (1u << 24)) return SKIPARSE_ESHAPE;

@@ -19,7 +19,7 @@
 //     matrix pipe and the vector ALU overlap within one wavefront as well as across the two on a SIMD.
 //   * In the steady state the instruction order of a step is written out by hand and fixed with scheduling fences:
 //     MFMAs of the two products alternate (so consecutive MFMAs never depend on each other), each followed by its share
-//     of the exponentials, and every LDS fragment is read three MFMAs before its use.
+//     of the exponentials, and every LDS fragment is read four MFMAs before its use (across the two steps of a window too).
 //   * Reference maximum without a per-block maximum: the exponentials are taken against the reference the row already
 //     has; the common path computes no maximum at all.  The guard is the row sum: if 16 probabilities of a lane add up
 //     to 2^16 or more (always on the first block, where the reference is -inf) the wavefront takes a rare path that finds
@@ -28,16 +28,16 @@
 //     result is exact up to rounding; probabilities up to 2^16 keep their relative precision in bf16, O and l are fp32.
 //   * K and V tiles of 64 keys go from global memory straight into LDS (global_load_lds_dwordx4, no staging registers,
 //     no LDS store instructions), double buffered, K one tile ahead of V (a window of two steps reads K tile W and V tile
-//     W-1), one barrier per window; the loads of a tile are enqueued a whole window before they are waited for.  LDS rows
-//     are packed (a direct load writes 64 consecutive 16-byte chunks) and bank conflicts are avoided by an XOR swizzle of
+//     W-1), one barrier per window; the loads of a tile are enqueued half a window before they are waited for (not earlier:
+//     see the window loop).  LDS rows are packed (a direct load writes 64 consecutive 16-byte chunks) and bank conflicts are avoided by an XOR swizzle of
 //     the chunk position with the row number, chosen so that both the 16-byte fragment reads of K (16 consecutive rows)
 //     and the transposing reads of V^T (ds_read_b64_tr_b16, 4 consecutive rows of 64 bytes) touch every bank once; V
 //     stays row-major in LDS.  (Three buffers with a two-window lead and a fence-free barrier measured slower.)
 //   * Row addresses come from the Skiparse index map: in the dense mode position j is row j, in the sparse modes it is
 //     the token the rearrangement (Algorithm 1) would have put at position j, so q, k, v are read and out is written in
-//     the original layout and no permuted copy exists.  A thread stages part of one row per tile and advances its
-//     (row, column) position by 64 keys with adds and one wrap, so the index arithmetic is a handful of full-rate
-//     24-bit multiply-adds per thread per 64 keys.
+//     the original layout and no permuted copy exists.  The rows' byte offsets are formed 8 tiles ahead, one tile (64 rows,
+//     lane = row) per window by one wavefront in turn, and kept in a small ring in LDS from which every lane picks up the
+//     two rows it fetches: the index arithmetic costs a wavefront one evaluation of the map per 8 tiles.
 //   * Workgroups are numbered so that the query tiles of one unit run on the same XCD (workgroup id mod 8 selects
 //     the XCD under round-robin dispatch; every XCD owns a contiguous eighth of the (unit, tile) order) and walk K/V in
 //     step: the per-XCD L2 then serves the re-reads.
@@ -91,12 +91,6 @@ __device__ inline void lane_pair(float x, float& lo, float& hi) {
     hi = __uint_as_float(r1);
 }
 
-// a*b + c on 24-bit unsigned operands (full-rate, unlike the 32-bit multiplies); operand ranges are checked on the host
-__device__ inline uint32_t mad24(uint32_t a, uint32_t b, uint32_t c) {
-    uint32_t r;
-    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
 // a value that is the same in every lane, moved to a scalar register
 __device__ inline uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ inline size_t uniform(size_t x) {

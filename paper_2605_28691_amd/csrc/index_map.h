@@ -52,8 +52,6 @@ struct GridMap {
     uint32_t b;
     uint32_t cmul; // c = p*cmul (rows) or q*cmul (columns)
     FastDiv ws;    // division by W/s
-    uint32_t step_r;  // 64 / (W/s) and 64 % (W/s): how (j / Ws, j % Ws) move when j advances by one 64-key tile
-    uint32_t step_w;
     FastDiv sdiv;  // division by s
     // Any-resolution mode (Sec. 3.2): positions enumerate the grid padded at the end of H and W to multiples of s*s;
     // H_real rows of every H_pad are real, and columns below W (the real row length above) are real.

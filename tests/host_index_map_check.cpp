@@ -20,8 +20,6 @@ static GridMap make(int T, int H, int W, int s, int group) {
     g.cmul = group ? (uint32_t)s : 1u;
     g.ws = make_fastdiv((uint32_t)(W / s));
     g.sdiv = make_fastdiv((uint32_t)s);
-    g.step_r = 64u / (uint32_t)(W / s);
-    g.step_w = 64u % (uint32_t)(W / s);
     return g;
 }
 
