@@ -20,6 +20,7 @@ SMALL = [  # B, heads, D, T, H, W, s -- several query/key tiles and ragged tails
     (1, 9, 128, 4, 9, 18, 3),    # s = 3, 9 heads (unit count not a multiple of 8)
     (1, 1, 128, 1, 16, 48, 4),   # s = 4: 16 subsequences of 48 tokens
     (1, 2, 128, 7, 16, 16, 2),   # Nsub = 448 = 7 * 64: no key tail
+    (1, 1, 64, 9, 24, 28, 2),    # Nsub = 1512: 24 key tiles, more than the 16 slots of the row-offset ring, tail of 40
 ]
 
 
@@ -171,6 +172,7 @@ PAD_CASES = [  # B, heads, D, T, H, W, s -- H or W not a multiple of s*s
     (1, 4, 128, 2, 11, 20, 3),
     (1, 2, 128, 6, 8, 12, 2),    # divisible: the padded mode must agree with the plain one
     (1, 1, 128, 9, 1, 33, 2),    # H = 1: the classes with p = 1 are empty
+    (1, 1, 64, 11, 21, 26, 2),   # padded grid 24 x 28: 1848 positions per class = 29 key tiles (ring wrap-around), rows of padding inside
 ]
 
 

@@ -23,6 +23,7 @@ SMALL = [  # B, heads, D, T, H, W, s
     (2, 2, 64, 5, 16, 20, 2),    # head_dim 64, batch of 2
     (1, 9, 128, 4, 9, 18, 3),    # s = 3, 9 heads
     (1, 2, 128, 7, 16, 16, 2),   # Nsub = 448 = 7 * 64: no tail
+    (1, 1, 64, 9, 24, 28, 2),    # Nsub = 1512: 24 streamed tiles, more than the 16 slots of the row-offset ring
 ]
 
 
@@ -151,6 +152,7 @@ PAD_CASES = [  # B, heads, D, T, H, W, s -- any-resolution mode: H or W not a mu
     (1, 2, 128, 9, 17, 21, 2),   # Nsub_pad = 9 * 5 * 6 = 270: two owner tiles, padding rows inside and at the end of tiles
     (1, 1, 128, 9, 1, 33, 2),    # H = 1: the classes with p = 1 hold padding only
     (1, 2, 128, 6, 8, 12, 2),    # divisible: must agree bit for bit with the plain mode
+    (1, 1, 64, 11, 21, 26, 2),   # padded grid 24 x 28: 29 streamed tiles (ring wrap-around), rows of padding inside
 ]
 
 
