@@ -169,6 +169,16 @@ def main() -> int:
             p_ms = time_calls(probe, 5, 2)
             extras[f"mfma_only_{name}_tflops"] = round(fl[0] / p_ms / 1e9, 1)
         result["roofline"]["attainable_mfma_only"] = extras["mfma_only_bf16_tflops"]
+        # the same with the A operand of every MFMA read from LDS, as an attention kernel must feed its products
+        lds_ops = rnd.to(torch.bfloat16).cuda()
+        fl = [0.0]
+
+        def lprobe():
+            fl[0] = sk.skiparse_mfma_lds_probe(lds_ops, sink, 512, 40000)
+
+        l_ms = time_calls(lprobe, 5, 2)
+        extras["mfma_lds_fed_bf16_tflops"] = round(fl[0] / l_ms / 1e9, 1)
+        result["roofline"]["attainable_mfma_lds_fed"] = extras["mfma_lds_fed_bf16_tflops"]
         # how much vector-ALU work the matrix pipe hides: the same loop on zero operands (full clock) with n independent FMAs per MFMA
         zero_ops = torch.zeros(8192, dtype=torch.bfloat16, device="cuda")
         for n in (0, 2, 4, 6, 8):

@@ -170,6 +170,15 @@ int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink,
 int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
                              int iters, double* flop, void* stream);
 
+/*
+ * Measurement aid: the bf16 MFMA loop (iters * 8 instructions per wavefront) in which the A operand of every MFMA is read from LDS
+ * with a 16-byte read per lane, the way an attention kernel feeds its matrix products (Sec. 3.1: the K and V tiles of a
+ * subsequence are shared by many queries).  Its rate on random operands is the ceiling for any LDS-fed kernel under the board's
+ * power management.  Buffers as for skiparse_mfma_probe.
+ */
+int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int blocks, int iters, double* flop,
+                            void* stream);
+
 /* Text for an error code; never NULL. */
 const char* skiparse_strerror(int code);
 

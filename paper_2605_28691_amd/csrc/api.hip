@@ -421,6 +421,15 @@ int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink,
     return finish(launch_mfma_probe(operands, sink, dtype == SKIPARSE_FP8_E4M3, blocks, iters, (hipStream_t)stream));
 }
 
+int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int blocks, int iters, double* flop,
+                            void* stream) {
+    if (!operands || !sink || misaligned(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    if (flop) *flop = 2.0 * 32 * 32 * 16 * 8.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
+    return finish(launch_mfma_lds_probe(operands, sink, blocks, iters, (hipStream_t)stream));
+}
+
 int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
                              int iters, double* flop, void* stream) {
     if (!operands || !sink || misaligned(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKIPARSE_EINVAL;

@@ -8,6 +8,7 @@ namespace skiparse {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr int PROBE_THREADS = 256;  // 4 wavefronts, one per SIMD; 512 workgroups put two wavefronts on every SIMD of 256 compute units
 constexpr int PROBE_FRAGS = 4;      // operand pairs cycled through, so that consecutive MFMAs see different data
@@ -80,6 +81,43 @@ __global__ __launch_bounds__(PROBE_THREADS) void mfma_valu_probe_kernel(const ch
 #pragma unroll
     for (int r = 0; r < 16; r++) s += acc0[r] + acc1[r] + v[r];
     sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
+}
+
+// Third probe: the bf16 MFMA loop with the A operand of EVERY MFMA read from LDS (ds_read_b128, 32 KiB of the caller's operands walked
+// in 8 KiB steps), as an attention kernel has to feed its matrix products; B operands cycle through 8 register fragments.
+__global__ __launch_bounds__(PROBE_THREADS) void mfma_lds_probe_kernel(const char* __restrict__ operands, float* __restrict__ sink, int iters) {
+    __shared__ __attribute__((aligned(16))) char lds[32768];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    for (uint32_t i = tid; i < 32768u / 16u; i += PROBE_THREADS) ((i32x4*)lds)[i] = *(const i32x4*)(operands + (i * 16u) % MFMA_PROBE_OPERAND_BYTES);
+    __syncthreads();
+    bf16x8 b[8];
+#pragma unroll
+    for (int f = 0; f < 8; f++) b[f] = *(const bf16x8*)(operands + ((size_t)f * 64 + lane) * 16);
+    f32x16 acc[PROBE_FRAGS];
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[f][r] = 0.f;
+    const char* base = lds + lane * 16u;
+    for (int it = 0; it < iters; it++) {
+        const char* p = base + (it & 3) * 8192;
+        bf16x8 a[8];
+#pragma unroll
+        for (int f = 0; f < 8; f++) a[f] = *(const bf16x8*)(p + f * 1024);
+#pragma unroll
+        for (int f = 0; f < 8; f++) acc[f % PROBE_FRAGS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], b[f], acc[f % PROBE_FRAGS], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) s += acc[f][r];
+    sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
+}
+
+hipError_t launch_mfma_lds_probe(const void* operands, float* sink, int blocks, int iters, hipStream_t stream) {
+    mfma_lds_probe_kernel<<<blocks, PROBE_THREADS, 0, stream>>>((const char*)operands, sink, iters);
+    return hipGetLastError();
 }
 
 hipError_t launch_mfma_valu_probe(const void* operands, float* sink, int valu_per_mfma, int blocks, int iters, hipStream_t stream) {

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
             "skiparse_switch_pattern", "skiparse_attn_fwd_sparse", "skiparse_attn_fwd_lse",
-            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes", "skiparse_mfma_probe", "skiparse_mfma_valu_probe"} <= set(names)
+            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes", "skiparse_mfma_probe", "skiparse_mfma_valu_probe", "skiparse_mfma_lds_probe"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -193,3 +193,6 @@ def test_mfma_probe_rejects_bad_arguments(lib):
     assert lib.skiparse_mfma_valu_probe(p, 1 << 20, q, 1 << 30, 3, 8, 10, ctypes.byref(flop), None) == -3   # only 0, 2, 4, 6, 8
     assert lib.skiparse_mfma_valu_probe(p, 1 << 20, q, 100, 4, 8, 10, ctypes.byref(flop), None) == -4
     assert lib.skiparse_mfma_valu_probe(None, 1 << 20, q, 1 << 30, 4, 8, 10, ctypes.byref(flop), None) == -1
+    assert lib.skiparse_mfma_lds_probe(None, 1 << 20, q, 1 << 30, 8, 10, ctypes.byref(flop), None) == -1
+    assert lib.skiparse_mfma_lds_probe(p, 100, q, 1 << 30, 8, 10, ctypes.byref(flop), None) == -4
+    assert lib.skiparse_mfma_lds_probe(p, 1 << 20, q, 1 << 30, 8, 0, ctypes.byref(flop), None) == -1

@@ -34,3 +34,15 @@ def test_mfma_valu_probe_runs():
         assert flop == 2.0 * 32 * 32 * 16 * 2 * 5 * 4 * 8
     torch.cuda.synchronize()
     assert bool(torch.isfinite(sink).all())
+
+
+def test_mfma_lds_probe_runs_and_counts_flop():
+    import paper_2605_28691_amd as sk
+
+    ops = torch.ones(8192, dtype=torch.bfloat16, device="cuda")  # every product is 1
+    sink = torch.full((8 * 256,), -1.0, dtype=torch.float32, device="cuda")
+    flop = sk.skiparse_mfma_lds_probe(ops, sink, 8, 6)
+    torch.cuda.synchronize()
+    assert flop == 2.0 * 32 * 32 * 16 * 8 * 6 * 4 * 8
+    # 8 MFMAs of depth 16 per iteration spread over 4 accumulators: every register = 16 * 2 * 6; a thread sums 4 x 16 registers
+    assert bool((sink == 4 * 16 * 16 * 2 * 6).all())
