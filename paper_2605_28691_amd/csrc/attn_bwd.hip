@@ -58,6 +58,11 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     constexpr int RPI = 64 / CH; // rows filled by one direct-to-LDS instruction of a wavefront
     constexpr int IPW = CH / BNW;  // such instructions per wavefront, tensor and tile
     constexpr bool DKV = MODE == BWD_DKV; // dK and dV together: two accumulators, the owner's second operand (V) lives in LDS
+    // dQ launch: LDS fragments are read AH MFMA groups before their use and the order is pinned with scheduling fences, so that
+    // an MFMA waits only for its own operands (-7 %).  The dK+dV launch has no registers to spare for fragments in flight (every
+    // such variant spilled into the MFMA chains and measured 8-30 % slower): there the order is left to the compiler.
+    constexpr int AH = 4;
+    constexpr bool MAN_A = !DKV, MAN_C = !DKV;
     constexpr int TILE_BYTES = BT * RB;
     static_assert(IPW >= 1 && IPW * BNW == CH, "a tile is CH instructions, spread evenly over the wavefronts");
     // two streamed tensors, double buffered; separate arrays so that the compiler can tell the tile being filled from the one
@@ -274,16 +279,49 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
                     m2[4 * g + e] = i2[e];
                 }
             }
+            // M1 and M2: their MFMA steps alternate (two independent accumulators)
+            constexpr int NA = 2 * KS;
+            auto frag_a = [&](int g) __attribute__((always_inline)) -> bf16x8 {
+                return *(const bf16x8*)((g % 2 == 0 ? t1 : t2) + a_rd(g / 2) + blk * 32 * RB);
+            };
+            bf16x8 fa[NA], oa[DKV ? KS : 1];
+            if (MAN_A) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-                const bf16x8 f1 = *(const bf16x8*)(t1 + a_rd(ks) + blk * 32 * RB);
-                m1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, own1[ks], m1, 0, 0, 0);
+                for (int g = 0; g < AH; g++) {
+                    fa[g] = frag_a(g);
+                    if (DKV && g % 2 == 1) oa[g / 2] = *(const bf16x8*)(own2_lds + a_rd(g / 2));
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-                const bf16x8 f2 = *(const bf16x8*)(t2 + a_rd(ks) + blk * 32 * RB);
-                const bf16x8 o2 = DKV ? *(const bf16x8*)(own2_lds + a_rd(ks)) : own2[DKV ? 0 : ks];
-                m2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, o2, m2, 0, 0, 0);
+            for (int g = 0; g < NA; g++) {
+                if (MAN_A) {
+                    if (g + AH < NA) {
+                        fa[g + AH] = frag_a(g + AH);
+                        if (DKV && (g + AH) % 2 == 1) oa[(g + AH) / 2] = *(const bf16x8*)(own2_lds + a_rd((g + AH) / 2));
+                    }
+                } else {
+                    fa[g] = frag_a(g);
+                    if (DKV && g % 2 == 1) oa[g / 2] = *(const bf16x8*)(own2_lds + a_rd(g / 2));
+                }
+                if (g % 2 == 0) m1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g], own1[g / 2], m1, 0, 0, 0);
+                else m2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g], DKV ? oa[DKV ? g / 2 : 0] : own2[DKV ? 0 : g / 2], m2, 0, 0, 0);
+                if (MAN_A) __builtin_amdgcn_sched_barrier(0);
+            }
+            // the last product's first fragments are fetched now, under the elementwise arithmetic
+            constexpr int NC = (DKV ? 4 : 2) * MT;  // DKV: dK and dV groups alternate
+            auto frag_c = [&](int cidx) __attribute__((always_inline)) -> bf16x8 {
+                const int pair = DKV ? cidx / 2 : cidx, g2 = pair / MT, mt = pair % MT;
+                const char* ta = ((DKV && cidx % 2 == 1) ? t2 : t1) + (blk * 32 + g2 * 16) * RB;  // dV reads the dO tile, dQ and dK the first tensor
+                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[0][mt]));
+                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[1][mt]));
+                return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+            };
+            bf16x8 fc[NC];
+            if (MAN_C) {
+#pragma unroll
+                for (int cidx = 0; cidx < AH; cidx++) fc[cidx] = frag_c(cidx);
+                __builtin_amdgcn_sched_barrier(0);
             }
             bf16x8 rf[2], rp[DKV ? 2 : 1];  // rp: P itself in the DKV launch (rf holds dS there)
 #pragma unroll
@@ -315,23 +353,19 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
                 rf[g2] = pk;
                 if (DKV) rp[g2] = pp;
             }
+            if (MAN_C) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int g2 = 0; g2 < 2; g2++)
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) {
-                    const char* ta = t1 + (blk * 32 + g2 * 16) * RB;  // A3 of dQ and dK: the first streamed tensor
-                    const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[0][mt]));
-                    const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[1][mt]));
-                    const bf16x8 tf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, rf[g2], acc[mt], 0, 0, 0);
-                    if (DKV) {  // dV^T += dO^T P with the dO tile
-                        const char* tb = t2 + (blk * 32 + g2 * 16) * RB;
-                        const bf16x4 w0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(tb + t_rd[0][mt]));
-                        const bf16x4 w1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(tb + t_rd[1][mt]));
-                        const bf16x8 tg = __builtin_shufflevector(w0, w1, 0, 1, 2, 3, 4, 5, 6, 7);
-                        acc2[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tg, rp[g2], acc2[mt], 0, 0, 0);
-                    }
+            for (int cidx = 0; cidx < NC; cidx++) {
+                if (MAN_C) {
+                    if (cidx + AH < NC) fc[cidx + AH] = frag_c(cidx + AH);
+                } else {
+                    fc[cidx] = frag_c(cidx);
                 }
+                const int pair = DKV ? cidx / 2 : cidx, g2 = pair / MT, mt = pair % MT;
+                if (DKV && cidx % 2 == 1) acc2[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[cidx], rp[DKV ? g2 : 0], acc2[mt], 0, 0, 0);  // dV^T += dO^T P
+                else acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fc[cidx], rf[g2], acc[mt], 0, 0, 0);
+                if (MAN_C) __builtin_amdgcn_sched_barrier(0);
+            }
         }
         if (more) store_rowvals(PARITY ^ 1);
         tile_landed();
