@@ -13,11 +13,14 @@
 //   * The probabilities leave the accumulators as 16 values per 32-key block in the accumulator's key order (4h..4h+3,
 //     8+4h..); packed to bytes, one v_permlane32_swap per 16 keys turns that into 8 consecutive keys per lane half,
 //     which is the order ds_read_b64_tr_b8 (transposing LDS read for bytes) delivers V^T in.
-//   * K rows are padded to D+16 bytes and V rows to D+32 bytes in LDS so that the 16-byte fragment reads and the
-//     transposing reads spread over the banks.
+//   * K/V tiles of 64 keys go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS
+//     stores), double buffered.  Rows are packed (head_dim bytes); the position of a row's 16-byte chunk is XOR-swizzled with
+//     the row number (lds_swizzle8) so that the 16-byte fragment reads of K (16 consecutive rows) and the transposing byte
+//     reads of V^T (8 rows x 32 bytes per phase) both touch every bank once.
 #include <type_traits>
 
 #include "kernels.h"
+#include "lds_layout.h"
 
 namespace skiparse {
 
@@ -50,19 +53,21 @@ __attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD8, WAVES_PER_SIMD8)))
 __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t total, uint32_t per_xcd) {
     constexpr int NJ = D / 64;         // 64-channel MFMA steps of S^T = K Q^T
     constexpr int MT = D / 32;         // 32-channel blocks of O^T
-    constexpr int K_STRIDE = D + 16;   // bytes
-    constexpr int V_STRIDE = D + 32;
-    constexpr int K_BYTES = KT8 * K_STRIDE, V_BYTES = KT8 * V_STRIDE;
+    constexpr int RB = D;              // row bytes in LDS (packed rows, swizzled chunk positions)
     constexpr int CH = D / 16;         // 16-byte chunks per row
-    constexpr int TPR_MAX = NT8 / KT8 >= 8 ? 8 : NT8 / KT8 >= 4 ? 4 : NT8 / KT8 >= 2 ? 2 : 1;
-    constexpr int TPR = TPR_MAX < CH ? TPR_MAX : CH;  // threads that stage one row of a tile (a power of two)
-    constexpr int CPT = CH / TPR;      // 16-byte chunks per staging thread
-    __shared__ __attribute__((aligned(16))) char lds[2 * K_BYTES + 2 * V_BYTES];
+    constexpr int RPI = 64 / CH;       // rows filled by one direct-to-LDS instruction of a wavefront
+    constexpr int IPW = CH >= NW8 ? CH / NW8 : 1;  // such instructions per wavefront, tensor and tile (with more wavefronts than instructions only the first CH stage)
+    constexpr int STAGERS = CH >= NW8 ? NW8 : CH;
+    constexpr int TILE_BYTES = KT8 * RB;
+    static_assert(IPW * STAGERS == CH, "a tile is CH instructions, spread evenly over the staging wavefronts");
+    // separate arrays so that the compiler can tell the tile being filled from the one being read
+    __shared__ __attribute__((aligned(1024))) char kbuf0[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char kbuf1[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char vbuf0[TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char vbuf1[TILE_BYTES];
     __shared__ float sv_part[NW8];
-    char* const lds_k = lds;
-    char* const lds_v = lds + 2 * K_BYTES;
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
     const uint32_t xcd = blockIdx.x & 7u, idx = blockIdx.x >> 3;
     const uint32_t lin = xcd * per_xcd + idx;  // each XCD owns a contiguous range of the (unit, tile) order
@@ -101,29 +106,28 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     const uint32_t q_blk = (qt * (32u * NW8) + wave * 32u) / 128u;
     const float cq = a.scale * 1.4426950408889634f * a.sq[(size_t)unit * n_blk + (q_blk < n_blk ? q_blk : n_blk - 1u)];
 
-    // staging: TPR threads per row of a 64-key tile, CPT consecutive 16-byte chunks each
-    const uint32_t st_row = (tid / TPR) % KT8, st_piece = tid % TPR;
-    const bool st_active = tid < KT8 * TPR;  // with short rows only part of the workgroup stages
-    u32x4 kreg[CPT], vreg[CPT];
-    auto load_tile = [&](uint32_t t) __attribute__((always_inline)) {
-        uint32_t j = t * KT8 + st_row;
-        j = j < n_seq ? j : n_seq - 1u;
-        const size_t off = (size_t)j * C + (st_piece * CPT) * 16;
-        if (!st_active) return;
+    // staging: lane l of a direct load fetches, for row l/CH of the instruction's RPI rows, the chunk that the swizzle puts at
+    // position l%CH; its 16 bytes land at the instruction's LDS base + 16*l
+    uint32_t st_row[IPW], st_cb[IPW];
 #pragma unroll
-        for (int i = 0; i < CPT; i++) {
-            kreg[i] = *(const u32x4*)(Kg + off + i * 16);
-            vreg[i] = *(const u32x4*)(Vg + off + i * 16);
+    for (int i = 0; i < IPW; i++) {
+        st_row[i] = (wave * IPW + i) * RPI + lane / CH;
+        st_cb[i] = ((lane % CH) ^ lds_swizzle8<D>(st_row[i])) * 16u;
+    }
+    auto issue_tile = [&](uint32_t t, char* kb, char* vb) __attribute__((always_inline)) {
+        if (STAGERS < NW8 && wave >= (uint32_t)STAGERS) return;
+#pragma unroll
+        for (int i = 0; i < IPW; i++) {
+            uint32_t j = t * KT8 + st_row[i];
+            j = j < n_seq ? j : n_seq - 1u;  // rows past the end repeat the last row; their logits are masked
+            const uint32_t off = j * (uint32_t)C + st_cb[i];  // fits 32 bits: checked on the host
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Kg + off),
+                                             (LDS_PTR(void))(kb + (wave * IPW + i) * 1024u), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vg + off),
+                                             (LDS_PTR(void))(vb + (wave * IPW + i) * 1024u), 16, 0, 0);
         }
     };
-    auto store_tile = [&](uint32_t buf) __attribute__((always_inline)) {
-        if (!st_active) return;
-#pragma unroll
-        for (int i = 0; i < CPT; i++) {
-            *(u32x4*)(lds_k + buf * K_BYTES + st_row * K_STRIDE + (st_piece * CPT + i) * 16) = kreg[i];
-            *(u32x4*)(lds_v + buf * V_BYTES + st_row * V_STRIDE + (st_piece * CPT + i) * 16) = vreg[i];
-        }
-    };
+    auto tile_landed = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     f32x16 oacc[MT];
 #pragma unroll
@@ -132,25 +136,33 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
         for (int r = 0; r < 16; r++) oacc[mt][r] = 0.f;
     float m_ref = -INFINITY, l_run = 0.f;  // m_ref in log2 units of the scaled logits
 
-    const uint32_t k_rd = lq * K_STRIDE + 32 * h;  // + kt*32*K_STRIDE + 64*j
+    // K fragment of 64-channel step j: row lq (+ 32*kt), chunks 4j + 2h and 4j + 2h + 1 at their swizzled positions (adding 32*kt
+    // to the row leaves the swizzle, which depends on the row's low four bits, unchanged)
+    // (the position of chunk 4j + e + 2h is that of chunk 2h with (4j + e) * 16 XORed in: one register, an XOR per read)
+    const uint32_t k_rd0 = lq * RB + ((2 * h) ^ lds_swizzle8<D>(lq)) * 16u;
     // transposing byte read: a 16-lane group covers 8 keys x 16 channels; lane i addresses key i/2, channels 8*(i%2)..
     const uint32_t li = lane & 15u, lgrp = (lane >> 4) & 1u;
-    const uint32_t v_rd = (8 * h + (li >> 1)) * V_STRIDE + lgrp * 16 + 8 * (li & 1u);  // + g16*16*V_STRIDE + mt*32
+    const uint32_t v_row = 8 * h + (li >> 1);  // + 16*g16 (same swizzle); chunk 2*mt + lgrp: XOR mt * 32 into the position of chunk lgrp
+    const uint32_t v_rd0 = v_row * RB + (lgrp ^ lds_swizzle8<D>(v_row)) * 16u + 8 * (li & 1u);
 
     const uint32_t n_kt = (n_seq + KT8 - 1) / KT8;
-    load_tile(0);
-    store_tile(0);
+    issue_tile(0, kbuf0, vbuf0);
+    tile_landed();
     __syncthreads();
 
     float sk_cur = skp[0], sv_cur = svp[0], sk_nxt, sv_nxt;
     // one key tile; LAST (compile time) marks the final tile, the only one that may hold keys past the end: the masking code must
     // not be in the other tiles' path at all (the compiler turns a run-time test into 32 compares and selects per tile)
-    auto tile_body = [&](auto LASTC, uint32_t t) __attribute__((always_inline)) {
+    // The parity of the tile (which buffers) is a compile-time constant as well.
+    auto tile_body = [&](auto LASTC, auto PARC, uint32_t t) __attribute__((always_inline)) {
         constexpr bool LAST = decltype(LASTC)::value;
+        constexpr int PARITY = decltype(PARC)::value;  // t & 1
         const bool more = !LAST;
-        if (more) load_tile(t + 1);
-        const char* kb = lds_k + (t & 1u) * K_BYTES;
-        const char* vb = lds_v + (t & 1u) * V_BYTES;
+        const char* kb = PARITY ? kbuf1 : kbuf0;
+        const char* vb = PARITY ? vbuf1 : vbuf0;
+        // the next tile's loads have the whole tile to land (enqueued after the QK products instead: 13 % slower; one workgroup of
+        // 12 wavefronts sharing a tile instead of three independent ones of 4: 7 % slower)
+        if (more) issue_tile(t + 1, PARITY ? kbuf0 : kbuf1, PARITY ? vbuf0 : vbuf1);
         const float ct = cq * sk_cur;        // logits -> log2 units for this key block
         const float pg = sv_cur * p_gain;    // V scale of this key block, relative to the largest, times the gain
         {   // the next tile's scales are fetched a tile ahead so that no tile waits for them
@@ -168,7 +180,9 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
             for (int r = 0; r < 16; r++) sacc[kt][r] = 0.f;
 #pragma unroll
             for (int j = 0; j < NJ; j++) {
-                const i32x8 kf = *(const i32x8*)(kb + k_rd + kt * 32 * K_STRIDE + 64 * j);
+                const i32x4 k0 = *(const i32x4*)(kb + (k_rd0 ^ (uint32_t)((4 * j) * 16)) + kt * 32 * RB);
+                const i32x4 k1 = *(const i32x4*)(kb + (k_rd0 ^ (uint32_t)((4 * j + 1) * 16)) + kt * 32 * RB);
+                const i32x8 kf = __builtin_shufflevector(k0, k1, 0, 1, 2, 3, 4, 5, 6, 7);
                 sacc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[j], sacc[kt], 0, 0, 0, 0, 0, 0);
             }
         }
@@ -246,19 +260,30 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
             i32x8 vf;
 #pragma unroll
             for (int g16 = 0; g16 < 4; g16++) {
-                const i32x2 t8 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(i32x2))(LDS_PTR(char))(vb + v_rd + g16 * 16 * V_STRIDE + mt * 32));
+                const i32x2 t8 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(i32x2))(LDS_PTR(char))(vb + (v_rd0 ^ (uint32_t)(mt * 32)) + g16 * 16 * RB));
                 vf[2 * g16] = t8[0];
                 vf[2 * g16 + 1] = t8[1];
             }
             oacc[mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vf, pb, oacc[mt], 0, 0, 0, 0, 0, 0);
         }
-        if (more) store_tile((t + 1) & 1u);
         sk_cur = sk_nxt;
         sv_cur = sv_nxt;
+        tile_landed();
         __syncthreads();
     };
-    for (uint32_t t = 0; t + 1 < n_kt; t++) tile_body(std::false_type{}, t);
-    tile_body(std::true_type{}, n_kt - 1u);
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    uint32_t t = 0;
+    for (; t + 2 < n_kt; t += 2) {
+        tile_body(std::false_type{}, P0{}, t);
+        tile_body(std::false_type{}, P1{}, t + 1u);
+    }
+    if (t + 1 < n_kt) {
+        tile_body(std::false_type{}, P0{}, t);
+        tile_body(std::true_type{}, P1{}, t + 1u);
+    } else {
+        tile_body(std::true_type{}, P0{}, t);
+    }
 
     // epilogue: O = O^T * sv_max / gain / l, bf16, scattered to the original layout
     float llo, lhi;

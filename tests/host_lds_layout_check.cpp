@@ -75,8 +75,66 @@ static int check() {
     return 0;
 }
 
+// The 8-bit tile of the fp8 kernel: rows of D bytes, 4 staging wavefronts, K fragments of 2 x 16 bytes per lane (row lq + 32*kt, chunks
+// 4j + 2h and 4j + 2h + 1), transposing byte reads (lane i of a 16-lane group: row i/2 (+8h, +16*g16), 8 bytes at 8*(i%2) of chunk
+// 2*mt + lgrp).
+template <int D>
+static int check8() {
+    constexpr int RB = D, CH = D / 16, NW = 4, RPI = 64 / CH, IPW = CH / NW, NJ = D / 64, MT = D / 32;
+    std::map<std::pair<int, int>, int> loc;
+    for (int wave = 0; wave < NW; wave++)
+        for (int i = 0; i < IPW; i++)
+            for (int lane = 0; lane < 64; lane++) {
+                const int ii = wave * IPW + i, row = ii * RPI + lane / CH;
+                const int c = (lane % CH) ^ (int)lds_swizzle8<D>(row);
+                if (loc.count({row, c})) return printf("fp8 D=%d: (row %d, chunk %d) fetched twice\n", D, row, c), 1;
+                loc[{row, c}] = ii * 1024 + lane * 16;
+            }
+    if ((int)loc.size() != 64 * CH) return printf("fp8 D=%d: %zu chunks staged, want %d\n", D, loc.size(), 64 * CH), 1;
+    for (auto& kv : loc)
+        if (kv.second != kv.first.first * RB + ((kv.first.second ^ (int)lds_swizzle8<D>(kv.first.first)) * 16))
+            return printf("fp8 D=%d: row %d chunk %d lands at %d\n", D, kv.first.first, kv.first.second, kv.second), 1;
+    auto conflicts = [](const std::vector<int>& addrs, int bytes, int lanes_per_pass) {
+        int worst = 0;
+        for (size_t g = 0; g < addrs.size(); g += lanes_per_pass) {
+            int hits[64] = {0};
+            for (int l = 0; l < lanes_per_pass; l++)
+                for (int b = 0; b < bytes / 4; b++) worst = std::max(worst, ++hits[(addrs[g + l] / 4 + b) % 64]);
+        }
+        return worst;
+    };
+    for (int kt = 0; kt < 2; kt++)
+        for (int j = 0; j < NJ; j++)
+            for (int e = 0; e < 2; e++) {
+                std::vector<int> addrs;
+                for (int lane = 0; lane < 64; lane++) {
+                    const int lq = lane & 31, h = lane >> 5;
+                    const int k_rd0 = lq * RB + (((2 * h) ^ (int)lds_swizzle8<D>(lq)) * 16);
+                    const int a = (k_rd0 ^ ((4 * j + e) * 16)) + kt * 32 * RB;  // the kernel's XOR form
+                    if (a != loc[{kt * 32 + lq, 4 * j + 2 * h + e}]) return printf("fp8 D=%d: fragment address j=%d e=%d lane=%d\n", D, j, e, lane), 1;
+                    addrs.push_back(a);
+                }
+                if (conflicts(addrs, 16, 16) != 1) return printf("fp8 D=%d: fragment read j=%d has bank conflicts\n", D, j), 1;
+            }
+    for (int g16 = 0; g16 < 4; g16++)
+        for (int mt = 0; mt < MT; mt++) {
+            std::vector<int> addrs;
+            for (int lane = 0; lane < 64; lane++) {
+                const int h = lane >> 5, li = lane & 15, lgrp = (lane >> 4) & 1;
+                const int v_row = 8 * h + (li >> 1);
+                const int v_rd0 = v_row * RB + ((lgrp ^ (int)lds_swizzle8<D>(v_row)) * 16) + 8 * (li & 1);
+                const int a = (v_rd0 ^ (mt * 32)) + g16 * 16 * RB;  // the kernel's XOR form
+                const int full_row = v_row + 16 * g16, byte0 = mt * 32 + lgrp * 16 + 8 * (li & 1);
+                if (a != loc[{full_row, byte0 / 16}] + byte0 % 16) return printf("fp8 D=%d: transposing address lane=%d\n", D, lane), 1;
+                addrs.push_back(a);
+            }
+            if (conflicts(addrs, 8, 32) != 1) return printf("fp8 D=%d: transposing read has bank conflicts\n", D), 1;
+        }
+    return 0;
+}
+
 int main() {
-    if (check<128>() || check<64>()) return 1;
+    if (check<128>() || check<64>() || check8<128>() || check8<64>()) return 1;
     printf("ok\n");
     return 0;
 }
