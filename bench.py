@@ -25,7 +25,7 @@ PEAK_FP8_TFLOPS = 5000.0
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the fused 768P kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/pmc_traffic_768p.txt):
 # FETCH_SIZE reads half the bytes of a copy kernel of known size on this chip, so it is scaled by 2.0; WRITE_SIZE by 1.0.
-MEASURED_TRAFFIC_BYTES = {"768p": (3.19021e6 * 2.0 + 826002.0) * 1024.0}
+MEASURED_TRAFFIC_BYTES = {"768p": (3.19152e6 * 2.0 + 839205.0) * 1024.0}
 # Paper context only (end-to-end model speed-ups on other hardware; Tab. 2): not comparable to a kernel figure.
 PAPER_CONTEXT = {"e2e_speedup_h200_bf16": 1.64, "e2e_speedup_ascend950pr_hif8_720p": 1.69, "e2e_speedup_ascend950pr_hif8_768p": 2.27}
 
