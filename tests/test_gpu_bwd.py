@@ -214,3 +214,21 @@ def test_backward_720p_one_unit():
             assert float((dk_sum.abs() / dk_abs).max()) <= 2e-2
             assert float((dv_sum - do_sum).abs().max()) <= 2e-2 * float(do_sum.abs().max())
         del out, lse, dq, dk, dv
+
+
+def test_backward_768p_one_unit_group():
+    """The benchmark's shape (21 x 48 x 80, s = 2), group-wise, 4 of the 40 heads: gradients of sampled tokens of one attention unit
+    (20,160 tokens) against the oracle, which walks the whole unit."""
+    import paper_2605_28691_amd as sk
+
+    w = si.make_shape("768p_bwd", 1, 4, 128, 21, 48, 80, 2, seed=12)
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    T, H, W, s = w.T, w.H, w.W, w.s
+    _, _, dq, dk, dv = _run(sk, q, k, v, dout, T, H, W, s, "group", w.scale)
+    b, head, n0 = 0, 2, 54321
+    p0, q0, _ = oracle.dst_index("group", s, T, H, W, n0)
+    toks = [n0] + [oracle.src_index("group", s, T, H, W, p0, q0, j) for j in (0, 255, 256, 10007, w.Nsub - 1)]
+    want = oracle.skiparse_attention_bwd_unit(*oracle_inputs(q, k, v), si.as_oracle_array(dout), b, head, toks, T, H, W, s, "group", w.scale)
+    for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+        assert_grad_close(to_np64(g[b, toks, head]), wnt, f"768p group {name}")
