@@ -21,6 +21,7 @@ SMALL = [  # B, heads, D, T, H, W, s -- several query/key tiles and ragged tails
     (1, 1, 128, 1, 16, 48, 4),   # s = 4: 16 subsequences of 48 tokens
     (1, 2, 128, 7, 16, 16, 2),   # Nsub = 448 = 7 * 64: no key tail
     (1, 1, 64, 9, 24, 28, 2),    # Nsub = 1512: 24 key tiles, more than the 16 slots of the row-offset ring, tail of 40
+    (2, 2, 64, 1, 2, 2, 2),      # one token per subsequence (token-wise only): out = v
 ]
 
 
