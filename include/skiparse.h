@@ -1,7 +1,7 @@
 /*
  * skiparse.h -- C ABI of the MI355X (gfx950) Skiparse-2D attention library.
  *
- * The library computes the forward pass of the sparse attention layer of OSP-Next (Sec. 3.1
+ * The library computes the forward pass, and the gradients, of the sparse attention layer of OSP-Next (Sec. 3.1
  * "Skiparse-2D Attention", Algorithm 1 "Skiparse Rearrange"): a (T,H,W) token grid is split into s*s
  * spatially strided subsequences (token-wise or group-wise), ordinary softmax attention runs inside
  * every subsequence, and the result is put back in the original token order.
