@@ -151,34 +151,6 @@ int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const 
                           void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
                           float scale, void* stream);
 
-/*
- * Measurement aid, not part of the method: enqueues a kernel that issues nothing but matrix-core instructions (32x32x16 bf16
- * for SKIPARSE_BF16, 32x32x64 fp8 for SKIPARSE_FP8_E4M3) on the caller's operand bytes, `blocks` workgroups of 4 wavefronts,
- * iters * 4 instructions per wavefront.  The benchmark times it to report what the matrix pipe sustains by itself on the
- * same kind of data (the clock is power-managed), next to the nominal peak.  operands: >= 2048 * 8 bytes of device memory
- * (random values of the element type); sink: >= blocks * 256 floats, overwritten.  *flop (host pointer, may be NULL) receives
- * the floating-point operations of one launch.
- */
-int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int dtype, int blocks, int iters,
-                        double* flop, void* stream);
-
-/*
- * Measurement aid: the bf16 MFMA loop (iters * 2 instructions per wavefront) with valu_per_mfma (0, 2, 4, 6 or 8) independent
- * v_fma_f32 after every MFMA.  Timed by the benchmark to show how much vector-ALU work the matrix pipe hides on this chip, which
- * is what limits a softmax fused between two matrix products.  Buffers as for skiparse_mfma_probe.
- */
-int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
-                             int iters, double* flop, void* stream);
-
-/*
- * Measurement aid: the bf16 MFMA loop (iters * 8 instructions per wavefront) in which the A operand of every MFMA is read from LDS
- * with a 16-byte read per lane, the way an attention kernel feeds its matrix products (Sec. 3.1: the K and V tiles of a
- * subsequence are shared by many queries).  Its rate on random operands is the ceiling for any LDS-fed kernel under the board's
- * power management.  Buffers as for skiparse_mfma_probe.
- */
-int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int blocks, int iters, double* flop,
-                            void* stream);
-
 /* Text for an error code; never NULL. */
 const char* skiparse_strerror(int code);
 

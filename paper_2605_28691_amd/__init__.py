@@ -69,12 +69,6 @@ def lib() -> ctypes.CDLL:
         L.skiparse_quantize_fp8.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
         L.skiparse_attn_fwd_fp8.restype = i
         L.skiparse_attn_fwd_fp8.argtypes = [vp] * 7 + [i] * 8 + [f, vp]
-        L.skiparse_mfma_probe.restype = i
-        L.skiparse_mfma_probe.argtypes = [vp, sz, vp, sz, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
-        L.skiparse_mfma_lds_probe.restype = i
-        L.skiparse_mfma_lds_probe.argtypes = [vp, sz, vp, sz, i, i, ctypes.POINTER(ctypes.c_double), vp]
-        L.skiparse_mfma_valu_probe.restype = i
-        L.skiparse_mfma_valu_probe.argtypes = [vp, sz, vp, sz, i, i, i, ctypes.POINTER(ctypes.c_double), vp]
         L.skiparse_strerror.restype = ctypes.c_char_p
         L.skiparse_strerror.argtypes = [i]
         L.skiparse_last_hip_error.restype = i
@@ -287,36 +281,3 @@ def skiparse_attn_fwd_fp8(q8, k8, v8, sq, sk, sv, T: int, H: int, W: int, s: int
         "skiparse_attn_fwd_fp8",
     )
     return out
-
-
-def skiparse_mfma_probe(operands: torch.Tensor, sink: torch.Tensor, fp8: bool, blocks: int, iters: int) -> float:
-    """Measurement aid: enqueues the matrix-core-only kernel on the operand bytes; returns the FLOP of the launch."""
-    flop = ctypes.c_double(0.0)
-    _check(
-        lib().skiparse_mfma_probe(_dev(operands, "operands"), operands.numel() * operands.element_size(), _dev(sink, "sink"),
-                                  sink.numel() * sink.element_size(), FP8_E4M3 if fp8 else BF16, blocks, iters, ctypes.byref(flop), _stream()),
-        "skiparse_mfma_probe",
-    )
-    return flop.value
-
-
-def skiparse_mfma_lds_probe(operands: torch.Tensor, sink: torch.Tensor, blocks: int, iters: int) -> float:
-    """Measurement aid: bf16 MFMA loop whose A operand is read from LDS for every MFMA; returns the FLOP of the launch."""
-    flop = ctypes.c_double(0.0)
-    _check(
-        lib().skiparse_mfma_lds_probe(_dev(operands, "operands"), operands.numel() * operands.element_size(), _dev(sink, "sink"),
-                                      sink.numel() * sink.element_size(), blocks, iters, ctypes.byref(flop), _stream()),
-        "skiparse_mfma_lds_probe",
-    )
-    return flop.value
-
-
-def skiparse_mfma_valu_probe(operands: torch.Tensor, sink: torch.Tensor, valu_per_mfma: int, blocks: int, iters: int) -> float:
-    """Measurement aid: bf16 MFMA loop with `valu_per_mfma` independent FMAs after every MFMA; returns the FLOP of the launch."""
-    flop = ctypes.c_double(0.0)
-    _check(
-        lib().skiparse_mfma_valu_probe(_dev(operands, "operands"), operands.numel() * operands.element_size(), _dev(sink, "sink"),
-                                       sink.numel() * sink.element_size(), valu_per_mfma, blocks, iters, ctypes.byref(flop), _stream()),
-        "skiparse_mfma_valu_probe",
-    )
-    return flop.value

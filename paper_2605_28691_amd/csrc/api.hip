@@ -64,42 +64,8 @@ int check_shape(int B, int heads, int T, int H, int W, int head_dim, int s, int 
     return SKIPARSE_OK;
 }
 
-GridMap make_dense_gridmap(size_t n) {
-    GridMap g;
-    g.mode = MODE_DENSE;
-    g.s = 1;
-    g.W = 0;
-    g.n_tok = (int)n;
-    g.n_sub = (int)n;
-    g.a = 1;
-    g.b = 0;
-    g.cmul = 0;
-    g.ws = make_fastdiv(0xffffffffu);  // multiplier 2: the quotient is 0 for every position below 2^31
-    g.H_real = 1;
-    g.hpad = make_fastdiv(1);
-    g.sdiv = make_fastdiv(1);
-    return g;
-}
-
 GridMap make_gridmap(int T, int H, int W, int s, int pattern, bool pad = false) {
-    const int n_tok = T * H * W;
-    if (s == 1) return make_dense_gridmap((size_t)n_tok);
-    const int Hp = pad ? (H + s * s - 1) / (s * s) * (s * s) : H;
-    const int Wp = pad ? (W + s * s - 1) / (s * s) * (s * s) : W;
-    GridMap g;
-    g.mode = pattern == SKIPARSE_TOKEN ? MODE_TOKEN : MODE_GROUP;
-    g.s = s;
-    g.W = W;
-    g.n_tok = n_tok;
-    g.n_sub = T * Hp * Wp / (s * s);
-    g.a = pattern == SKIPARSE_TOKEN ? (uint32_t)s : 1u;
-    g.b = pattern == SKIPARSE_TOKEN ? 0u : (uint32_t)(s * s - s);
-    g.cmul = pattern == SKIPARSE_TOKEN ? 1u : (uint32_t)s;
-    g.ws = make_fastdiv((uint32_t)(Wp / s));
-    g.sdiv = make_fastdiv((uint32_t)s);
-    g.H_real = H;
-    g.hpad = make_fastdiv((uint32_t)Hp);
-    return g;
+    return skiparse::make_gridmap(T, H, W, s, pattern == SKIPARSE_GROUP, pad);
 }
 
 int finish(hipError_t e) {
@@ -401,6 +367,10 @@ int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const 
     if (overlap2(out_bf16, sh.elems * 2, q8, sh.elems) || overlap2(out_bf16, sh.elems * 2, k8, sh.elems) ||
         overlap2(out_bf16, sh.elems * 2, v8, sh.elems))
         return SKIPARSE_EINVAL;
+    // one float per (subsequence, head, 128 positions); the kernel reads them while it writes out
+    const size_t scale_bytes = (size_t)s * s * B * heads * ((sh.n_sub + 127) / 128) * sizeof(float);
+    for (const float* sc : {sq, sk, sv})
+        if ((reinterpret_cast<uintptr_t>(sc) & 3u) || overlap2(out_bf16, sh.elems * 2, sc, scale_bytes)) return SKIPARSE_EINVAL;
     Fp8AttnArgs a;
     a.q8 = q8; a.k8 = k8; a.v8 = v8; a.sq = sq; a.sk = sk; a.sv = sv; a.out = out_bf16;
     a.B = B; a.heads = heads; a.head_dim = head_dim;
@@ -408,36 +378,6 @@ int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const 
     a.n_blk = (uint32_t)((sh.n_sub + 127) / 128);
     a.g = make_gridmap(T, H, W, s, pattern);
     return finish(launch_attn_fp8(a, (hipStream_t)stream));
-}
-
-int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int dtype, int blocks, int iters,
-                        double* flop, void* stream) {
-    if (!operands || !sink || misaligned(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKIPARSE_EINVAL;
-    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
-    if (dtype != SKIPARSE_BF16 && dtype != SKIPARSE_FP8_E4M3) return SKIPARSE_EUNSUPPORTED;
-    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
-    const double per_mfma = dtype == SKIPARSE_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 64;
-    if (flop) *flop = per_mfma * 4.0 /* per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
-    return finish(launch_mfma_probe(operands, sink, dtype == SKIPARSE_FP8_E4M3, blocks, iters, (hipStream_t)stream));
-}
-
-int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int blocks, int iters, double* flop,
-                            void* stream) {
-    if (!operands || !sink || misaligned(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKIPARSE_EINVAL;
-    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
-    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
-    if (flop) *flop = 2.0 * 32 * 32 * 16 * 8.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
-    return finish(launch_mfma_lds_probe(operands, sink, blocks, iters, (hipStream_t)stream));
-}
-
-int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
-                             int iters, double* flop, void* stream) {
-    if (!operands || !sink || misaligned(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKIPARSE_EINVAL;
-    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
-    if (valu_per_mfma < 0 || valu_per_mfma > 8 || (valu_per_mfma & 1)) return SKIPARSE_EUNSUPPORTED;
-    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
-    if (flop) *flop = 2.0 * 32 * 32 * 16 * 2.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
-    return finish(launch_mfma_valu_probe(operands, sink, valu_per_mfma, blocks, iters, (hipStream_t)stream));
 }
 
 const char* skiparse_strerror(int code) {

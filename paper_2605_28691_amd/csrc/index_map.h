@@ -12,6 +12,7 @@
 // token j) uses a = 1, b = 0, c = 0 and a divisor of 2^31 so that r is always 0.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace skiparse {
@@ -79,6 +80,46 @@ __host__ __device__ inline uint32_t src_token_padded(const GridMap& g, uint32_t 
     const uint32_t h = row - t * g.hpad.d;
     *real = h < (uint32_t)g.H_real && w < (uint32_t)g.W;
     return (t * (uint32_t)g.H_real + h) * (uint32_t)g.W + w;
+}
+
+// Host side: the map of a grid.  `group` selects the group-wise pattern; `pad` the any-resolution mode, in which the
+// subsequences are those of the grid padded at the end of H and W to the next multiples of s*s.
+inline GridMap make_dense_gridmap(size_t n) {
+    GridMap g;
+    g.mode = MODE_DENSE;
+    g.s = 1;
+    g.W = 0;
+    g.n_tok = (int)n;
+    g.n_sub = (int)n;
+    g.a = 1;
+    g.b = 0;
+    g.cmul = 0;
+    g.ws = make_fastdiv(0xffffffffu);  // multiplier 2: the quotient is 0 for every position below 2^31
+    g.H_real = 1;
+    g.hpad = make_fastdiv(1);
+    g.sdiv = make_fastdiv(1);
+    return g;
+}
+
+inline GridMap make_gridmap(int T, int H, int W, int s, bool group, bool pad = false) {
+    const int n_tok = T * H * W;
+    if (s == 1) return make_dense_gridmap((size_t)n_tok);
+    const int Hp = pad ? (H + s * s - 1) / (s * s) * (s * s) : H;
+    const int Wp = pad ? (W + s * s - 1) / (s * s) * (s * s) : W;
+    GridMap g;
+    g.mode = group ? MODE_GROUP : MODE_TOKEN;
+    g.s = s;
+    g.W = W;
+    g.n_tok = n_tok;
+    g.n_sub = T * Hp * Wp / (s * s);
+    g.a = group ? 1u : (uint32_t)s;
+    g.b = group ? (uint32_t)(s * s - s) : 0u;
+    g.cmul = group ? (uint32_t)s : 1u;
+    g.ws = make_fastdiv((uint32_t)(Wp / s));
+    g.sdiv = make_fastdiv((uint32_t)s);
+    g.H_real = H;
+    g.hpad = make_fastdiv((uint32_t)Hp);
+    return g;
 }
 
 }  // namespace skiparse

@@ -86,12 +86,4 @@ struct Fp8AttnArgs {
 };
 hipError_t launch_attn_fp8(const Fp8AttnArgs& a, hipStream_t stream);
 
-// Measurement aid: `blocks` workgroups of 4 wavefronts, each wavefront issuing iters * 4 matrix-core instructions
-// (32x32x16 bf16, or 32x32x64 fp8 when fp8 != 0) on the caller's operand bytes; one float per thread is written to sink.
-constexpr int MFMA_PROBE_OPERAND_BYTES = 4 * 2 * 64 * 32;
-hipError_t launch_mfma_probe(const void* operands, float* sink, int fp8, int blocks, int iters, hipStream_t stream);
-// Same bf16 loop, iters * 2 MFMAs per wavefront, with valu_per_mfma (0, 2, 4, 6 or 8) independent v_fma_f32 after every MFMA.
-hipError_t launch_mfma_lds_probe(const void* operands, float* sink, int blocks, int iters, hipStream_t stream);
-hipError_t launch_mfma_valu_probe(const void* operands, float* sink, int valu_per_mfma, int blocks, int iters, hipStream_t stream);
-
 }  // namespace skiparse

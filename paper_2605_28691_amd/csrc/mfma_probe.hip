@@ -1,9 +1,18 @@
 // Measurement aid: a loop of nothing but matrix-core instructions on caller-supplied operands.  It shows what the matrix pipe
 // of this chip sustains by itself under the board's power management (on random operands the clock drops well below nominal),
 // which is the ceiling the attention kernels are judged against besides the nominal peak.
-#include "kernels.h"
+//
+// Built into a library of its own (libskiparse_probe.so, declared in include/skiparse_probe.h): the benchmark and one GPU test load
+// it; the attention library does not contain it.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
-namespace skiparse {
+#include "../../include/skiparse_probe.h"
+
+namespace skiparse_probe {
+
+constexpr int MFMA_PROBE_OPERAND_BYTES = 4 * 2 * 64 * 32;  // what the kernels read of the caller's operand buffer
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -115,12 +124,12 @@ __global__ __launch_bounds__(PROBE_THREADS) void mfma_lds_probe_kernel(const cha
     sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
 }
 
-hipError_t launch_mfma_lds_probe(const void* operands, float* sink, int blocks, int iters, hipStream_t stream) {
+static hipError_t launch_mfma_lds_probe(const void* operands, float* sink, int blocks, int iters, hipStream_t stream) {
     mfma_lds_probe_kernel<<<blocks, PROBE_THREADS, 0, stream>>>((const char*)operands, sink, iters);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_valu_probe(const void* operands, float* sink, int valu_per_mfma, int blocks, int iters, hipStream_t stream) {
+static hipError_t launch_mfma_valu_probe(const void* operands, float* sink, int valu_per_mfma, int blocks, int iters, hipStream_t stream) {
     const char* ops = (const char*)operands;
     switch (valu_per_mfma) {
         case 0: mfma_valu_probe_kernel<0><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
@@ -133,7 +142,7 @@ hipError_t launch_mfma_valu_probe(const void* operands, float* sink, int valu_pe
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_probe(const void* operands, float* sink, int fp8, int blocks, int iters, hipStream_t stream) {
+static hipError_t launch_mfma_probe(const void* operands, float* sink, int fp8, int blocks, int iters, hipStream_t stream) {
     if (fp8)
         mfma_probe_kernel<true><<<blocks, PROBE_THREADS, 0, stream>>>((const char*)operands, sink, iters);
     else
@@ -141,4 +150,61 @@ hipError_t launch_mfma_probe(const void* operands, float* sink, int fp8, int blo
     return hipGetLastError();
 }
 
-}  // namespace skiparse
+thread_local int g_last_hip_error = 0;
+
+static int finish(hipError_t e) {
+    if (e == hipSuccess) return SKIPARSE_OK;
+    g_last_hip_error = (int)e;
+    return SKIPARSE_EHIP;
+}
+
+static bool bad_buffers(const void* operands, const float* sink) {
+    return !operands || !sink || (reinterpret_cast<uintptr_t>(operands) & 15u) != 0 || (reinterpret_cast<uintptr_t>(sink) & 3u) != 0;
+}
+
+}  // namespace skiparse_probe
+
+using namespace skiparse_probe;
+
+extern "C" {
+
+int skiparse_mfma_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int dtype, int blocks, int iters,
+                        double* flop, void* stream) {
+    if (bad_buffers(operands, sink)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (dtype != SKIPARSE_BF16 && dtype != SKIPARSE_FP8_E4M3) return SKIPARSE_EUNSUPPORTED;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    const double per_mfma = dtype == SKIPARSE_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 64;
+    if (flop) *flop = per_mfma * 4.0 /* per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
+    return finish(launch_mfma_probe(operands, sink, dtype == SKIPARSE_FP8_E4M3, blocks, iters, (hipStream_t)stream));
+}
+
+int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int blocks, int iters, double* flop,
+                            void* stream) {
+    if (bad_buffers(operands, sink)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    if (flop) *flop = 2.0 * 32 * 32 * 16 * 8.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
+    return finish(launch_mfma_lds_probe(operands, sink, blocks, iters, (hipStream_t)stream));
+}
+
+int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
+                             int iters, double* flop, void* stream) {
+    if (bad_buffers(operands, sink)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (valu_per_mfma < 0 || valu_per_mfma > 8 || (valu_per_mfma & 1)) return SKIPARSE_EUNSUPPORTED;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    if (flop) *flop = 2.0 * 32 * 32 * 16 * 2.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
+    return finish(launch_mfma_valu_probe(operands, sink, valu_per_mfma, blocks, iters, (hipStream_t)stream));
+}
+
+int skiparse_probe_device_info(int device, int* compute_units, int* clock_khz) {
+    if (device < 0 || !compute_units || !clock_khz) return SKIPARSE_EINVAL;
+    hipError_t e = hipDeviceGetAttribute(compute_units, hipDeviceAttributeMultiprocessorCount, device);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(clock_khz, hipDeviceAttributeClockRate, device);
+    return finish(e);
+}
+
+int skiparse_probe_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -8,7 +8,9 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "skiparse.h")
+PROBE_HEADER = os.path.join(ROOT, "include", "skiparse_probe.h")
 LIBPATH = os.path.join(ROOT, "paper_2605_28691_amd", "libskiparse.so")
+PROBE_LIBPATH = os.path.join(ROOT, "paper_2605_28691_amd", "libskiparse_probe.so")
 
 
 @pytest.fixture(scope="module")
@@ -22,8 +24,19 @@ def lib():
     return sk.lib()
 
 
-def _declared_functions():
-    text = open(HEADER).read()
+@pytest.fixture(scope="module")
+def probe_lib():
+    from paper_2605_28691_amd import probe
+
+    if not os.path.exists(PROBE_LIBPATH):
+        from paper_2605_28691_amd import build
+
+        build.build()
+    return probe.lib()
+
+
+def _declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
 
@@ -33,9 +46,18 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
             "skiparse_switch_pattern", "skiparse_attn_fwd_sparse", "skiparse_attn_fwd_lse",
-            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes", "skiparse_mfma_probe", "skiparse_mfma_valu_probe", "skiparse_mfma_lds_probe"} <= set(names)
+            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
+    assert not [n for n in names if "probe" in n]  # the measurement kernels live in a library of their own
+
+
+def test_every_declared_probe_symbol_is_exported(probe_lib):
+    names = _declared_functions(PROBE_HEADER)
+    assert {"skiparse_mfma_probe", "skiparse_mfma_valu_probe", "skiparse_mfma_lds_probe", "skiparse_probe_device_info",
+            "skiparse_probe_last_hip_error"} <= set(names)
+    for n in names:
+        assert hasattr(probe_lib, n), n
 
 
 def test_strerror(lib):
@@ -116,6 +138,8 @@ def test_fp8_entry_points_reject_bad_arguments(lib):
     assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], a[5], a[0], *ok, f, None) == -1  # out aliases q8
     assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], a[5], a[6], 1, 2, 2, 8, 8, 32, 2, 0, f, None) == -3
     assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], a[5], a[6], 1, 2, 2, 8, 7, 64, 2, 0, f, None) == -2
+    assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], ctypes.c_void_p(FAKE + 2), a[4], a[5], a[6], *ok, f, None) == -1  # misaligned scales
+    assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], ctypes.c_void_p(a[6].value + 64), a[6], *ok, f, None) == -1  # scales inside out
 
 
 def test_attention_rejects_out_of_range_sizes(lib):
@@ -182,7 +206,8 @@ def test_backward_rejects_bad_arguments(lib):
     assert lib.skiparse_attn_fwd_lse(a[0], a[1], a[2], a[3], a[4], 1, 2, 2, 8, 6, 64, 2, 1, f, 0, 0, None) == -2  # group-wise needs W % 4 == 0
 
 
-def test_mfma_probe_rejects_bad_arguments(lib):
+def test_mfma_probe_rejects_bad_arguments(probe_lib):
+    lib = probe_lib
     p, q = ctypes.c_void_p(FAKE), ctypes.c_void_p(FAKE + (1 << 30))
     flop = ctypes.c_double(0.0)
     assert lib.skiparse_mfma_probe(None, 1 << 20, q, 1 << 30, 0, 8, 10, ctypes.byref(flop), None) == -1
@@ -196,3 +221,6 @@ def test_mfma_probe_rejects_bad_arguments(lib):
     assert lib.skiparse_mfma_lds_probe(None, 1 << 20, q, 1 << 30, 8, 10, ctypes.byref(flop), None) == -1
     assert lib.skiparse_mfma_lds_probe(p, 100, q, 1 << 30, 8, 10, ctypes.byref(flop), None) == -4
     assert lib.skiparse_mfma_lds_probe(p, 1 << 20, q, 1 << 30, 8, 0, ctypes.byref(flop), None) == -1
+    assert lib.skiparse_probe_device_info(0, None, None) == -1
+    assert lib.skiparse_probe_device_info(-1, ctypes.byref(ctypes.c_int()), ctypes.byref(ctypes.c_int())) == -1
+
