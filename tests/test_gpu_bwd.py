@@ -237,3 +237,27 @@ def test_backward_768p_one_unit_group():
     want = oracle.skiparse_attention_bwd_unit(*oracle_inputs(q, k, v), si.as_oracle_array(dout), b, head, toks, T, H, W, s, "group", w.scale)
     for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
         assert_grad_close(to_np64(g[b, toks, head]), wnt, f"768p group {name}")
+
+
+def test_backward_768p_one_unit_token_all_heads():
+    """The call bench.py times: the 768P workload itself (40 heads, seed 2), token-wise.  Gradients of sampled tokens of one
+    attention unit against the oracle, plus the any-size invariants for every head of one subsequence."""
+    import paper_2605_28691_amd as sk
+
+    w = si.WORKLOADS["768p"]
+    q, k, v = si.make_qkv(w)
+    dout = si.make_dout(w)
+    T, H, W, s = w.T, w.H, w.W, w.s
+    _, _, dq, dk, dv = _run(sk, q, k, v, dout, T, H, W, s, "token", w.scale)
+    b, head, n0 = 0, 37, 70001
+    p0, q0, _ = oracle.dst_index("token", s, T, H, W, n0)
+    toks = [n0] + [oracle.src_index("token", s, T, H, W, p0, q0, j) for j in (0, 255, 256, 12345, w.Nsub - 1)]
+    want = oracle.skiparse_attention_bwd_unit(*oracle_inputs(q, k, v), si.as_oracle_array(dout), b, head, toks, T, H, W, s, "token", w.scale)
+    for g, wnt, name in zip((dq, dk, dv), want, ("dq", "dk", "dv")):
+        ma, rl = assert_grad_close(to_np64(g[b, toks, head]), wnt, f"768p token {name}")
+        print(f"768p token-wise {name}: max-abs {ma:.3e} rel-L2 {rl:.3e}")
+    idx = torch.tensor([oracle.src_index("token", s, T, H, W, p0, q0, j) for j in range(w.Nsub)], device="cuda")
+    dk_sum, dk_abs = dk[0, idx].double().sum(0), dk[0, idx].double().abs().sum(0)
+    dv_sum, do_sum = dv[0, idx].double().sum(0), dout.cuda()[0, idx].double().sum(0)
+    assert float((dk_sum.abs() / dk_abs).max()) <= 2e-2
+    assert float((dv_sum - do_sum).abs().max()) <= 2e-2 * float(do_sum.abs().max())
