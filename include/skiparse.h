@@ -132,6 +132,26 @@ int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* o
                       int dtype, unsigned flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The backward pass for callers that cannot allocate device memory (code under HIP graph capture, tight serving or training
+ * loops, harnesses that forbid hipMalloc): skiparse_attn_bwd with the delta workspace taken from a static device array inside the
+ * library instead of a caller's buffer.  The call allocates nothing and frees nothing; inputs, outputs and results are exactly
+ * those of skiparse_attn_bwd.
+ *   Limit: the workspace the call would need (skiparse_bwd_workspace_bytes()) must not exceed SKIPARSE_STATIC_SCRATCH_BYTES
+ *   (16 MiB = 4,194,304 positions x heads x subsequences; the 768P shape with 40 heads needs 12.9 MB); larger problems are
+ *   rejected with SKIPARSE_EWORKSPACE and must use skiparse_attn_bwd.  Every GPU the library is used on holds the array until
+ *   the process ends.
+ *   The array is shared by all calls on a GPU and keeps the last call's contents (every element a call reads it has written
+ *   itself first, so nothing needs clearing): calls that overlap in time on one GPU, e.g. on two streams, race; serialise them.
+ *   The device address of the array is looked up on the first call on each device (hipGetSymbolAddress; that first call must
+ *   not itself be under graph capture).
+ */
+enum { SKIPARSE_STATIC_SCRATCH_BYTES = 16 * 1024 * 1024 };
+size_t skiparse_static_scratch_bytes(void);
+int skiparse_attn_bwd_static(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
+                             void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
+                             int dtype, unsigned flags, void* stream);
+
+/*
  * 8-bit variant (motivated by Sec. 3.5, which runs the attention MatMuls in an 8-bit format; here OCP fp8 e4m3
  * with fine-grained scales instead of per-tensor HiF8).
  * skiparse_quantize_fp8: x (bf16, ORIGINAL layout) -> x8 (e4m3fn bytes, SPARSE layout) and

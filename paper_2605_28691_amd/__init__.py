@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.skiparse_bwd_workspace_bytes.argtypes = [i] * 8 + [u]
         L.skiparse_attn_bwd.restype = i
         L.skiparse_attn_bwd.argtypes = [vp] * 9 + [i] * 8 + [f, i, u, vp, sz, vp]
+        L.skiparse_attn_bwd_static.restype = i
+        L.skiparse_attn_bwd_static.argtypes = [vp] * 9 + [i] * 8 + [f, i, u, vp]
+        L.skiparse_static_scratch_bytes.restype = sz
+        L.skiparse_static_scratch_bytes.argtypes = []
         L.skiparse_workspace_bytes.restype = sz
         L.skiparse_workspace_bytes.argtypes = [i] * 8 + [u]
         L.skiparse_quantize_fp8.restype = i
@@ -244,6 +248,20 @@ def skiparse_attn_bwd(q, k, v, out, dout, lse, T: int, H: int, W: int, s: int, p
                                 _DTYPES[q.dtype], PAD if pad else 0, _dev(workspace, "workspace"),
                                 workspace.numel() * workspace.element_size(), _stream()),
         "skiparse_attn_bwd",
+    )
+    return dq, dk, dv
+
+
+def skiparse_attn_bwd_static(q, k, v, out, dout, lse, dq, dk, dv, T: int, H: int, W: int, s: int, pattern: str, scale: float = 0.0,
+                             pad: bool = False):
+    """skiparse_attn_bwd for callers that cannot allocate: the delta workspace is the library's static device array, and this
+    wrapper allocates nothing either (dq, dk, dv must be passed).  Problems above the array's size raise (code -4)."""
+    B, heads, D = _dims(q, T, H, W)
+    _check(
+        lib().skiparse_attn_bwd_static(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), _dev(dout, "dout"), _dev(lse, "lse"),
+                                       _dev(dq, "dq"), _dev(dk, "dk"), _dev(dv, "dv"), B, heads, T, H, W, D, s, PATTERNS[pattern],
+                                       float(scale), _DTYPES[q.dtype], PAD if pad else 0, _stream()),
+        "skiparse_attn_bwd_static",
     )
     return dq, dk, dv
 

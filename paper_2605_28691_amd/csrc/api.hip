@@ -4,13 +4,26 @@
 
 #include <stdint.h>
 
+#include <mutex>
+
 #include "kernels.h"
 
 using namespace skiparse;
 
+// Scratch of skiparse_attn_bwd_static (the backward pass for callers that cannot allocate): the delta array, one float per
+// (subsequence, head, position).  Every GPU the library runs on holds its own copy at its own address until the process ends.
+// In host code this name is only a stand-in for the symbol: the device address is looked up once per device (static_scratch())
+// and that pointer, never the name, is what the kernels get.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)SKIPARSE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};  // device address of `scratch` on each device, filled on the first call there
+std::mutex g_scratch_mutex;
 
 int elem_size(int dtype) {
     switch (dtype) {
@@ -72,6 +85,24 @@ int finish(hipError_t e) {
     if (e == hipSuccess) return SKIPARSE_OK;
     g_last_hip_error = (int)e;
     return SKIPARSE_EHIP;
+}
+
+// Device address of the static scratch on the CURRENT device: looked up once per device, with that device current, and kept.
+int static_scratch(void** ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return finish(e);
+    if (dev < 0 || dev >= MAX_DEVICES) return SKIPARSE_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return finish(e);
+        if (p == nullptr) return finish(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return SKIPARSE_OK;
 }
 
 int permute_common(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
@@ -296,9 +327,11 @@ size_t skiparse_bwd_workspace_bytes(int B, int heads, int T, int H, int W, int h
     return align256(skiparse_lse_bytes(B, heads, T, H, W, head_dim, s, pattern, flags));
 }
 
-int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
-                      void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
-                      int dtype, unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
+// Shared by skiparse_attn_bwd (caller's workspace) and skiparse_attn_bwd_static (workspace == nullptr: the library's static scratch,
+// whose device address is looked up after the arguments have been validated).
+static int attn_bwd_common(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
+                           void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
+                           int dtype, unsigned flags, void* workspace, size_t workspace_bytes, bool use_static, void* stream) {
     if (flags & ~(unsigned)SKIPARSE_PAD) return SKIPARSE_EINVAL;
     const bool pad = (flags & SKIPARSE_PAD) != 0 && s > 1;
     Shape sh;
@@ -317,7 +350,13 @@ int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* o
         if (!y || misaligned(y)) return SKIPARSE_EINVAL;
     if (!lse || ((uintptr_t)lse & 3u)) return SKIPARSE_EINVAL;
     const size_t need = align256(lse_bytes);
-    if (!workspace || workspace_bytes < need || misaligned(workspace)) return SKIPARSE_EWORKSPACE;
+    if (use_static) {
+        if (need > STATIC_SCRATCH_BYTES) return SKIPARSE_EWORKSPACE;  // the problem is larger than the static scratch
+        rc = static_scratch(&workspace);
+        if (rc != SKIPARSE_OK) return rc;
+    } else if (!workspace || workspace_bytes < need || misaligned(workspace)) {
+        return SKIPARSE_EWORKSPACE;
+    }
     // no gradient may alias an input, another gradient, the log-sum-exp or the workspace
     for (int i = 0; i < 3; i++) {
         for (const void* x : ins)
@@ -338,6 +377,22 @@ int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* o
     a.pad = pad;
     a.g = make_gridmap(T, H, W, s, pattern, pad);
     return finish(launch_attn_bwd_bf16(a, (hipStream_t)stream));
+}
+
+int skiparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
+                      void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
+                      int dtype, unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
+    return attn_bwd_common(q, k, v, out, dout, lse, dq, dk, dv, B, heads, T, H, W, head_dim, s, pattern, scale, dtype, flags, workspace,
+                           workspace_bytes, false, stream);
+}
+
+size_t skiparse_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int skiparse_attn_bwd_static(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse, void* dq,
+                             void* dk, void* dv, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern, float scale,
+                             int dtype, unsigned flags, void* stream) {
+    return attn_bwd_common(q, k, v, out, dout, lse, dq, dk, dv, B, heads, T, H, W, head_dim, s, pattern, scale, dtype, flags, nullptr, 0,
+                           true, stream);
 }
 
 int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
@@ -386,7 +441,7 @@ const char* skiparse_strerror(int code) {
         case SKIPARSE_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, unknown enum, overlapping buffers)";
         case SKIPARSE_ESHAPE: return "grid not divisible as the pattern requires, or sizes out of range";
         case SKIPARSE_EUNSUPPORTED: return "no kernel for this head_dim / element type";
-        case SKIPARSE_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case SKIPARSE_EWORKSPACE: return "workspace missing, misaligned or too small (or, for the static-scratch entry point, the problem exceeds the scratch)";
         case SKIPARSE_EHIP: return "kernel launch failed (see skiparse_last_hip_error)";
         default: return "unknown error code";
     }

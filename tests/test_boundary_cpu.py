@@ -46,7 +46,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"skiparse_permute", "skiparse_unpermute", "dense_attn_fwd", "skiparse_attn_fwd", "skiparse_workspace_bytes",
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
             "skiparse_switch_pattern", "skiparse_attn_fwd_sparse", "skiparse_attn_fwd_lse",
-            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes"} <= set(names)
+            "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes", "skiparse_attn_bwd_static",
+            "skiparse_static_scratch_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert not [n for n in names if "probe" in n]  # the measurement kernels live in a library of their own
@@ -224,3 +225,17 @@ def test_mfma_probe_rejects_bad_arguments(probe_lib):
     assert lib.skiparse_probe_device_info(0, None, None) == -1
     assert lib.skiparse_probe_device_info(-1, ctypes.byref(ctypes.c_int()), ctypes.byref(ctypes.c_int())) == -1
 
+
+def test_static_scratch_backward_rejects_what_does_not_fit(lib):
+    """skiparse_attn_bwd_static: a problem whose delta array exceeds the static scratch is refused before any HIP call, and bad
+    arguments are refused like skiparse_attn_bwd's."""
+    assert lib.skiparse_static_scratch_bytes() == 16 * 1024 * 1024
+    ptrs = [ctypes.c_void_p(FAKE + (i << 34)) for i in range(9)]
+    f = ctypes.c_float(0.0)
+    # B = 2 at the 768P shape: 2 * 40 * 80640 floats = 25.8 MB > 16 MiB
+    rc = lib.skiparse_attn_bwd_static(*ptrs, 2, 40, 21, 48, 80, 128, 2, 0, f, 0, 0, None)
+    assert rc == -4 and b"scratch" in lib.skiparse_strerror(rc)
+    assert lib.skiparse_attn_bwd_static(*ptrs[:8], None, 1, 2, 2, 8, 8, 64, 2, 0, f, 0, 0, None) == -1
+    assert lib.skiparse_attn_bwd_static(*ptrs, 1, 2, 2, 8, 6, 64, 2, 1, f, 0, 0, None) == -2   # group-wise needs W % 4 == 0
+    assert lib.skiparse_attn_bwd_static(*ptrs, 1, 2, 2, 8, 8, 96, 2, 0, f, 0, 0, None) == -3   # head_dim 96
+    assert lib.skiparse_attn_bwd_static(*ptrs, 1, 2, 2, 8, 8, 64, 2, 0, f, 0, 4, None) == -1   # unknown flag
