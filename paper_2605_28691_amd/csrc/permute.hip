@@ -10,21 +10,53 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int PERMUTE_WAVES = 4;  // rows per workgroup
 
-template <int UNROLL>
+// BY_ORIG = false: the wavefronts enumerate the rows of the SPARSE layout (consecutive wavefronts touch consecutive sparse rows) and
+// find each row's place in the original layout with the index map; BY_ORIG = true: they enumerate the rows of the ORIGINAL layout
+// and find each token's class and position with the inverse formulas.  Either serves both directions; what differs is which
+// side of the copy is contiguous across wavefronts.  Contiguous WRITES with gathered reads measure faster than the reverse, so
+// the permute (writes the sparse layout) enumerates sparse rows and the unpermute (writes the original layout) original rows.
+template <int UNROLL, bool BY_ORIG>
 __global__ __launch_bounds__(PERMUTE_WAVES * 64) void permute_rows_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
                                                                           int B, GridMap g, uint32_t chunks_per_row,
                                                                           uint32_t n_rows, int to_sparse) {
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t row = blockIdx.x * PERMUTE_WAVES + (threadIdx.x >> 6);  // row number in the sparse layout
+    const uint32_t row = blockIdx.x * PERMUTE_WAVES + (threadIdx.x >> 6);
     if (row >= n_rows) return;
-    // sparse row -> (sb, j) -> (p, q, b) -> row number in the original layout
-    const uint32_t n_sub = (uint32_t)g.n_sub;
-    const uint32_t sb = row / n_sub, j = row - sb * n_sub;
-    const uint32_t pq = sb / (uint32_t)B, b = sb - pq * (uint32_t)B;
-    const uint32_t p = pq / (uint32_t)g.s, q = pq - p * (uint32_t)g.s;
-    const uint32_t orig_row = b * (uint32_t)g.n_tok + src_token(g, p, q, j);
-    const u32x4* s = src + (size_t)(to_sparse ? orig_row : row) * chunks_per_row;
-    u32x4* d = dst + (size_t)(to_sparse ? row : orig_row) * chunks_per_row;
+    uint32_t sparse_row, orig_row;
+    if (!BY_ORIG) {
+        // sparse row -> (sb, j) -> (p, q, b) -> row number in the original layout
+        sparse_row = row;
+        const uint32_t n_sub = (uint32_t)g.n_sub;
+        const uint32_t sb = row / n_sub, j = row - sb * n_sub;
+        const uint32_t pq = sb / (uint32_t)B, b = sb - pq * (uint32_t)B;
+        const uint32_t p = pq / (uint32_t)g.s, q = pq - p * (uint32_t)g.s;
+        orig_row = b * (uint32_t)g.n_tok + src_token(g, p, q, j);
+    } else {
+        // original row -> (b, t*H + h, w) -> class (p, q) and position (Alg. 1 read backwards; H and W are multiples of s for the
+        // token-wise pattern and of s*s for the group-wise one, so t*H + h splits like h)
+        orig_row = row;
+        sparse_row = row;
+        if (g.mode != MODE_DENSE) {
+            const uint32_t s = (uint32_t)g.s, W = (uint32_t)g.W;
+            const uint32_t b = row / (uint32_t)g.n_tok, n = row - b * (uint32_t)g.n_tok;
+            const uint32_t th = n / W, w = n - th * W;
+            uint32_t p, q, r, ws;
+            if (g.mode == MODE_GROUP) {
+                p = (th / s) % s;
+                q = (w / s) % s;
+                r = (th / (s * s)) * s + th % s;
+                ws = (w / (s * s)) * s + w % s;
+            } else {
+                p = th % s;
+                q = w % s;
+                r = th / s;
+                ws = w / s;
+            }
+            sparse_row = ((p * s + q) * (uint32_t)B + b) * (uint32_t)g.n_sub + r * (W / s) + ws;
+        }
+    }
+    const u32x4* s = src + (size_t)(to_sparse ? orig_row : sparse_row) * chunks_per_row;
+    u32x4* d = dst + (size_t)(to_sparse ? sparse_row : orig_row) * chunks_per_row;
     uint32_t c = lane;
     for (; c + (UNROLL - 1) * 64u < chunks_per_row; c += UNROLL * 64u) {
         u32x4 tmp[UNROLL];
@@ -91,18 +123,35 @@ hipError_t launch_switch(const void* src, void* dst, int B, const GridMap& g_to,
     return hipGetLastError();
 }
 
+#ifndef SKIPARSE_UNPERMUTE_BY_ORIG
+#define SKIPARSE_UNPERMUTE_BY_ORIG 1
+#endif
+#ifndef SKIPARSE_PERMUTE_BY_ORIG
+#define SKIPARSE_PERMUTE_BY_ORIG 0
+#endif
+
+template <int UNROLL>
+static void launch_rows(const void* src, void* dst, int B, const GridMap& g, uint32_t chunks, uint32_t n_rows, int to_sparse,
+                        hipStream_t stream) {
+    const uint32_t blocks = (n_rows + PERMUTE_WAVES - 1) / PERMUTE_WAVES;
+    const bool by_orig = to_sparse ? SKIPARSE_PERMUTE_BY_ORIG : SKIPARSE_UNPERMUTE_BY_ORIG;
+    if (by_orig)
+        permute_rows_kernel<UNROLL, true><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+    else
+        permute_rows_kernel<UNROLL, false><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+}
+
 hipError_t launch_permute(const void* src, void* dst, int B, const GridMap& g, size_t row_bytes, int to_sparse,
                           hipStream_t stream) {
     const uint32_t chunks = (uint32_t)(row_bytes / 16);
     const uint32_t s2 = g.mode == MODE_DENSE ? 1u : (uint32_t)(g.s * g.s);
     const uint32_t n_rows = (uint32_t)B * s2 * (uint32_t)g.n_sub;
-    const uint32_t blocks = (n_rows + PERMUTE_WAVES - 1) / PERMUTE_WAVES;
     if (chunks >= 5 * 64)
-        permute_rows_kernel<5><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+        launch_rows<5>(src, dst, B, g, chunks, n_rows, to_sparse, stream);
     else if (chunks >= 3 * 64)
-        permute_rows_kernel<3><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+        launch_rows<3>(src, dst, B, g, chunks, n_rows, to_sparse, stream);
     else
-        permute_rows_kernel<1><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+        launch_rows<1>(src, dst, B, g, chunks, n_rows, to_sparse, stream);
     return hipGetLastError();
 }
 
