@@ -256,7 +256,17 @@ def main() -> int:
 
             v_ms = time_calls(vprobe, 3)["avg"]
             extras[f"mfma_zero_operands_with_{n}_fma_per_mfma_tflops"] = round(fl[0] / v_ms / 1e9, 1)
-        del sink
+        # what the LDS delivers to the two kinds of fragment read the attention kernels use (nominal clock assumed: the probe draws little power)
+        sink2 = torch.empty(512 * 512, dtype=torch.float32, device="cuda")
+        for kind, name in ((0, "ds_read_b128"), (1, "ds_read_b64_tr_b16")):
+            nb = [0.0]
+
+            def rprobe():
+                nb[0] = probe.lds_read_probe(lds_ops, sink2, kind, 512, 20000)
+
+            r_ms = time_calls(rprobe, 3)["avg"]
+            extras[f"lds_{name}_bytes_per_clk_per_cu"] = round(nb[0] / (r_ms * 1e-3) / cus / (clock_khz * 1e3), 1)
+        del sink, sink2
     it = max(5, min(10, args.steps))
     tensor_bytes = qd.numel() * 2
     if "group" in sections and "group" in w.patterns:

@@ -43,6 +43,15 @@ int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* 
 int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int blocks, int iters, double* flop,
                             void* stream);
 
+/*
+ * LDS read instructions only, addressed as the attention kernels address a staged tile of 64 rows of 128 bf16 values: kind 0 = the
+ * 16-byte fragment reads (ds_read_b128), kind 1 = the transposing reads (ds_read_b64_tr_b16), kind 2 = plain 8-byte reads at the
+ * transposing reads' addresses.  `blocks` workgroups of 8 wavefronts, iters * 16 reads per wavefront.  sink: >= blocks * 512 floats.
+ * *bytes (host pointer, may be NULL) receives the bytes read from LDS by one launch.
+ */
+int skiparse_lds_read_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int kind, int blocks, int iters,
+                            double* bytes, void* stream);
+
 /* Compute units and nominal engine clock (kHz) of HIP device `device`, as the runtime reports them (host pointers). */
 int skiparse_probe_device_info(int device, int* compute_units, int* clock_khz);
 

@@ -9,6 +9,7 @@
 #include <stdint.h>
 
 #include "../../include/skiparse_probe.h"
+#include "lds_layout.h"
 
 namespace skiparse_probe {
 
@@ -124,6 +125,74 @@ __global__ __launch_bounds__(PROBE_THREADS) void mfma_lds_probe_kernel(const cha
     sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
 }
 
+// Fourth probe: LDS read instructions only, addressed exactly as the attention kernels address a staged tile of 64 rows of 128 bf16
+// (packed rows, XOR-swizzled chunk positions): KIND 0 = the 16-byte fragment reads of K (ds_read_b128, 1 KiB per wavefront
+// instruction), KIND 1 = the transposing reads of V^T (ds_read_b64_tr_b16, 512 bytes per wavefront instruction), KIND 2 = plain
+// 8-byte reads at the transposing reads' addresses.  16 reads per iteration, all independent; the values are folded into one word
+// per thread so that nothing is optimised away.  Timed by the benchmark: bytes per clock and compute unit that each kind of read
+// sustains, which bounds how fast an LDS-fed matrix product can be supplied.
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+#define PROBE_LDS_PTR(T) __attribute__((address_space(3))) T*
+
+template <int KIND>
+__global__ __launch_bounds__(512) void lds_read_probe_kernel(const char* __restrict__ operands, float* __restrict__ sink, int iters) {
+    constexpr int RB = 256;  // row bytes of a 128-channel bf16 tile
+    __shared__ __attribute__((aligned(1024))) char tile[2][64 * RB];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    for (uint32_t i = tid; i < 2u * 64u * RB / 16u; i += 512u) ((i32x4*)&tile[0][0])[i] = *(const i32x4*)(operands + (i * 16u) % MFMA_PROBE_OPERAND_BYTES);
+    __syncthreads();
+    const uint32_t lq = lane & 31u, h = lane >> 5, li = lane & 15u, lgrp = (lane >> 4) & 1u;
+    uint32_t k_rd[8], v_rd[2][4];
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) k_rd[ks] = lq * RB + (((uint32_t)(2 * ks) + h) ^ skiparse::lds_swizzle<128>(lq)) * 16u;
+#pragma unroll
+    for (int sec = 0; sec < 2; sec++)
+#pragma unroll
+        for (int mt = 0; mt < 4; mt++) {
+            const uint32_t row = 4 * h + (li >> 2) + 8 * sec;
+            const uint32_t ch = (uint32_t)(mt * 4) + lgrp * 2 + ((li & 3u) >> 1);
+            v_rd[sec][mt] = row * RB + ((ch ^ skiparse::lds_swizzle<128>(row)) * 16u) + 8 * (li & 1u);
+        }
+    int fold = 0;
+    for (int it = 0; it < iters; it++) {
+        const char* t = &tile[it & 1][0] + ((it >> 1) & 1) * 32 * RB;  // the two 32-row halves of the two tiles in turn
+        if (KIND == 0) {
+            i32x4 f[16];
+#pragma unroll
+            for (int g = 0; g < 16; g++) f[g] = *(const i32x4*)(&tile[it & 1][0] + k_rd[g & 7] + (g >> 3) * 32 * RB);
+#pragma unroll
+            for (int g = 0; g < 16; g++) fold ^= f[g][0] ^ f[g][3];
+        } else if (KIND == 1) {
+            bf16x4 f[16];
+#pragma unroll
+            for (int g = 0; g < 16; g++)
+                f[g] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((PROBE_LDS_PTR(bf16x4))(PROBE_LDS_PTR(char))(t + v_rd[g & 1][(g >> 1) & 3] + (g >> 3) * 16 * RB));
+#pragma unroll
+            for (int g = 0; g < 16; g++) fold ^= __builtin_bit_cast(i32x2, f[g])[0] ^ __builtin_bit_cast(i32x2, f[g])[1];
+        } else {
+            i32x2 f[16];
+#pragma unroll
+            for (int g = 0; g < 16; g++) f[g] = *(const i32x2*)(t + v_rd[g & 1][(g >> 1) & 3] + (g >> 3) * 16 * RB);
+#pragma unroll
+            for (int g = 0; g < 16; g++) fold ^= f[g][0] ^ f[g][1];
+        }
+        asm volatile("" : "+v"(fold)::"memory");  // the reads of the next iteration may not be merged with these
+    }
+    sink[(size_t)blockIdx.x * 512 + tid] = (float)(fold & 0xffff);
+}
+
+static hipError_t launch_lds_read_probe(const void* operands, float* sink, int kind, int blocks, int iters, hipStream_t stream) {
+    const char* ops = (const char*)operands;
+    switch (kind) {
+        case 0: lds_read_probe_kernel<0><<<blocks, 512, 0, stream>>>(ops, sink, iters); break;
+        case 1: lds_read_probe_kernel<1><<<blocks, 512, 0, stream>>>(ops, sink, iters); break;
+        case 2: lds_read_probe_kernel<2><<<blocks, 512, 0, stream>>>(ops, sink, iters); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 static hipError_t launch_mfma_lds_probe(const void* operands, float* sink, int blocks, int iters, hipStream_t stream) {
     mfma_lds_probe_kernel<<<blocks, PROBE_THREADS, 0, stream>>>((const char*)operands, sink, iters);
     return hipGetLastError();
@@ -196,6 +265,16 @@ int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* 
     if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
     if (flop) *flop = 2.0 * 32 * 32 * 16 * 2.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
     return finish(launch_mfma_valu_probe(operands, sink, valu_per_mfma, blocks, iters, (hipStream_t)stream));
+}
+
+int skiparse_lds_read_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int kind, int blocks, int iters,
+                            double* bytes, void* stream) {
+    if (bad_buffers(operands, sink)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (kind < 0 || kind > 2) return SKIPARSE_EUNSUPPORTED;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 512 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    if (bytes) *bytes = (kind == 0 ? 1024.0 : 512.0) * 16.0 /* reads per iteration */ * iters * 8.0 /* wavefronts */ * blocks;
+    return finish(launch_lds_read_probe(operands, sink, kind, blocks, iters, (hipStream_t)stream));
 }
 
 int skiparse_probe_device_info(int device, int* compute_units, int* clock_khz) {

@@ -27,6 +27,8 @@ def lib() -> ctypes.CDLL:
         L.skiparse_mfma_lds_probe.argtypes = [vp, sz, vp, sz, i, i, pd, vp]
         L.skiparse_mfma_valu_probe.restype = i
         L.skiparse_mfma_valu_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
+        L.skiparse_lds_read_probe.restype = i
+        L.skiparse_lds_read_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
         L.skiparse_probe_device_info.restype = i
         L.skiparse_probe_device_info.argtypes = [i, ctypes.POINTER(i), ctypes.POINTER(i)]
         L.skiparse_probe_last_hip_error.restype = i
@@ -73,6 +75,13 @@ def mfma_valu_probe(operands: torch.Tensor, sink: torch.Tensor, valu_per_mfma: i
     _check(lib().skiparse_mfma_valu_probe(*_args(operands, sink), valu_per_mfma, blocks, iters, ctypes.byref(flop), _stream()),
            "skiparse_mfma_valu_probe")
     return flop.value
+
+
+def lds_read_probe(operands: torch.Tensor, sink: torch.Tensor, kind: int, blocks: int, iters: int) -> float:
+    """LDS reads only (0: 16-byte fragment reads, 1: transposing reads, 2: plain 8-byte reads); returns the bytes read by the launch."""
+    nbytes = ctypes.c_double(0.0)
+    _check(lib().skiparse_lds_read_probe(*_args(operands, sink), kind, blocks, iters, ctypes.byref(nbytes), _stream()), "skiparse_lds_read_probe")
+    return nbytes.value
 
 
 def device_info(device: int = 0):

@@ -54,3 +54,15 @@ def test_device_info_reports_the_mi355x():
     cu, khz = probe.device_info(0)
     assert cu == torch.cuda.get_device_properties(0).multi_processor_count
     assert 1_000_000 <= khz <= 3_000_000  # nominal engine clock in kHz (2.4 GHz on MI355X)
+
+
+def test_lds_read_probe_runs_and_counts_bytes():
+    from paper_2605_28691_amd import probe
+
+    ops = torch.ones(8192, dtype=torch.bfloat16, device="cuda")
+    sink = torch.full((4 * 512,), -1.0, dtype=torch.float32, device="cuda")
+    for kind, per_read in ((0, 1024), (1, 512), (2, 512)):
+        nbytes = probe.lds_read_probe(ops, sink, kind, 4, 3)
+        assert nbytes == per_read * 16 * 3 * 8 * 4
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all()) and bool((sink >= 0).all())
