@@ -58,11 +58,25 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
     constexpr int RPI = 64 / CH; // rows filled by one direct-to-LDS instruction of a wavefront
     constexpr int IPW = CH / BNW;  // such instructions per wavefront, tensor and tile
     constexpr bool DKV = MODE == BWD_DKV; // dK and dV together: two accumulators, the owner's second operand (V) lives in LDS
-    // dQ launch: LDS fragments are read AH MFMA groups before their use and the order is pinned with scheduling fences, so that
-    // an MFMA waits only for its own operands (-7 %).  The dK+dV launch has no registers to spare for fragments in flight (every
-    // such variant spilled into the MFMA chains and measured 8-30 % slower): there the order is left to the compiler.
-    constexpr int AH = 4;
-    constexpr bool MAN_A = !DKV, MAN_C = !DKV;
+    // LDS fragments are read a few MFMA groups before their use and the order is pinned with scheduling fences, so that an MFMA
+    // waits only for its own operands (left to itself the compiler issues each read right before the MFMA that needs it).  The dQ
+    // launch reads 4 groups ahead (-7 %).  The dK+dV launch has almost no registers to spare: 1 group ahead in the first two
+    // products and 2 in the last two is what fits without spilling into the MFMA chains (-2 %; deeper variants spill and measure
+    // 2-14 % slower).  The depths of the dK+dV launch can be overridden at build time for measurements.
+#ifndef BWD_DKV_MAN_A
+#define BWD_DKV_MAN_A 1
+#endif
+#ifndef BWD_DKV_MAN_C
+#define BWD_DKV_MAN_C 1
+#endif
+#ifndef BWD_DKV_AH_A
+#define BWD_DKV_AH_A 1
+#endif
+#ifndef BWD_DKV_AH_C
+#define BWD_DKV_AH_C 2
+#endif
+    constexpr int AH_A = DKV ? BWD_DKV_AH_A : 4, AH_C = DKV ? BWD_DKV_AH_C : 4;
+    constexpr bool MAN_A = DKV ? (BWD_DKV_MAN_A != 0) : true, MAN_C = DKV ? (BWD_DKV_MAN_C != 0) : true;
     constexpr int TILE_BYTES = BT * RB;
     static_assert(IPW >= 1 && IPW * BNW == CH, "a tile is CH instructions, spread evenly over the wavefronts");
     // two streamed tensors, double buffered; separate arrays so that the compiler can tell the tile being filled from the one
@@ -287,7 +301,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             bf16x8 fa[NA], oa[DKV ? KS : 1];
             if (MAN_A) {
 #pragma unroll
-                for (int g = 0; g < AH; g++) {
+                for (int g = 0; g < AH_A; g++) {
                     fa[g] = frag_a(g);
                     if (DKV && g % 2 == 1) oa[g / 2] = *(const bf16x8*)(own2_lds + a_rd(g / 2));
                 }
@@ -296,9 +310,9 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 #pragma unroll
             for (int g = 0; g < NA; g++) {
                 if (MAN_A) {
-                    if (g + AH < NA) {
-                        fa[g + AH] = frag_a(g + AH);
-                        if (DKV && (g + AH) % 2 == 1) oa[(g + AH) / 2] = *(const bf16x8*)(own2_lds + a_rd((g + AH) / 2));
+                    if (g + AH_A < NA) {
+                        fa[g + AH_A] = frag_a(g + AH_A);
+                        if (DKV && (g + AH_A) % 2 == 1) oa[(g + AH_A) / 2] = *(const bf16x8*)(own2_lds + a_rd((g + AH_A) / 2));
                     }
                 } else {
                     fa[g] = frag_a(g);
@@ -320,7 +334,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             bf16x8 fc[NC];
             if (MAN_C) {
 #pragma unroll
-                for (int cidx = 0; cidx < AH; cidx++) fc[cidx] = frag_c(cidx);
+                for (int cidx = 0; cidx < AH_C; cidx++) fc[cidx] = frag_c(cidx);
                 __builtin_amdgcn_sched_barrier(0);
             }
             bf16x8 rf[2], rp[DKV ? 2 : 1];  // rp: P itself in the DKV launch (rf holds dS there)
@@ -357,7 +371,7 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
 #pragma unroll
             for (int cidx = 0; cidx < NC; cidx++) {
                 if (MAN_C) {
-                    if (cidx + AH < NC) fc[cidx + AH] = frag_c(cidx + AH);
+                    if (cidx + AH_C < NC) fc[cidx + AH_C] = frag_c(cidx + AH_C);
                 } else {
                     fc[cidx] = frag_c(cidx);
                 }
