@@ -76,8 +76,8 @@ def write_traffic(dirs, commit):
                 vals[row["Counter_Name"]][row["Kernel_Name"]].append(float(row["Counter_Value"]))
     out = {"commit": commit, "workload": "768p", "kernel": HEADLINE_KERNEL, "copy_kernel_kib": copy_kib}
     for ctr in ("FETCH_SIZE", "WRITE_SIZE"):
-        head = [v for k, v in vals[ctr].items() if k.startswith(HEADLINE_KERNEL)]
-        cp = [v for k, v in vals[ctr].items() if k.startswith(COPY_KERNEL)]
+        head = [v for k, v in vals[ctr].items() if HEADLINE_KERNEL in k]
+        cp = [v for k, v in sorted(vals[ctr].items()) if COPY_KERNEL in k]
         if not head or not cp:
             raise SystemExit(f"bench.py: {ctr} of {HEADLINE_KERNEL} or {COPY_KERNEL} not found under {dirs}")
         head_kib = sum(head[0]) / len(head[0])
