@@ -44,6 +44,13 @@ int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* s
                             void* stream);
 
 /*
+ * The bf16 loop with `chain` (1, 2, 4 or 8) consecutive MFMAs on the same accumulator before moving to the next of four
+ * (iters * 4 * chain instructions per wavefront): whether accumulator reuse inside the matrix pipe changes its sustained rate.
+ */
+int skiparse_mfma_chain_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int chain, int blocks, int iters,
+                              double* flop, void* stream);
+
+/*
  * LDS read instructions only, addressed as the attention kernels address a staged tile of 64 rows of 128 bf16 values: kind 0 = the
  * 16-byte fragment reads (ds_read_b128), kind 1 = the transposing reads (ds_read_b64_tr_b16), kind 2 = plain 8-byte reads at the
  * transposing reads' addresses.  `blocks` workgroups of 8 wavefronts, iters * 16 reads per wavefront.  sink: >= blocks * 512 floats.

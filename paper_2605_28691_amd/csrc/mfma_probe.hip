@@ -58,6 +58,51 @@ __global__ __launch_bounds__(PROBE_THREADS) void mfma_probe_kernel(const char* _
     sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
 }
 
+// The bf16 loop with CHAIN consecutive MFMAs on the SAME accumulator before moving to the next of the four (CHAIN = 1 is
+// mfma_probe_kernel's round robin): shows whether keeping an accumulator in the matrix pipe for several instructions in a row changes
+// what the pipe sustains under the power limit (register-file traffic of the accumulators) and how dependent issue behaves.
+template <int CHAIN>
+__global__ __launch_bounds__(PROBE_THREADS) void mfma_chain_probe_kernel(const char* __restrict__ operands, float* __restrict__ sink, int iters) {
+    const uint32_t lane = threadIdx.x & 63u;
+    bf16x8 a[PROBE_FRAGS], b[PROBE_FRAGS];
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++) {
+        a[f] = *(const bf16x8*)(operands + ((size_t)(2 * f) * 64 + lane) * 32);
+        b[f] = *(const bf16x8*)(operands + ((size_t)(2 * f + 1) * 64 + lane) * 32);
+    }
+    f32x16 acc[PROBE_FRAGS];
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[f][r] = 0.f;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int f = 0; f < PROBE_FRAGS; f++)
+#pragma unroll
+            for (int c = 0; c < CHAIN; c++)
+                acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(f + c) % PROBE_FRAGS], b[(f + c + 1) % PROBE_FRAGS], acc[f], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int f = 0; f < PROBE_FRAGS; f++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) s += acc[f][r];
+    sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
+}
+
+static hipError_t launch_mfma_chain_probe(const void* operands, float* sink, int chain, int blocks, int iters, hipStream_t stream) {
+    const char* ops = (const char*)operands;
+    switch (chain) {
+        case 1: mfma_chain_probe_kernel<1><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        case 2: mfma_chain_probe_kernel<2><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        case 4: mfma_chain_probe_kernel<4><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        case 8: mfma_chain_probe_kernel<8><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // Second probe: the same bf16 MFMA loop with NV independent v_fma_f32 per MFMA in between (fences keep the order).  Shows how much
 // vector-ALU work the matrix pipe hides: on this chip a 32x32x16 MFMA keeps the vector issue port busy for about 20 of its 32
 // clocks, so only about three full-rate vector instructions per MFMA are free.
@@ -265,6 +310,16 @@ int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* 
     if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
     if (flop) *flop = 2.0 * 32 * 32 * 16 * 2.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
     return finish(launch_mfma_valu_probe(operands, sink, valu_per_mfma, blocks, iters, (hipStream_t)stream));
+}
+
+int skiparse_mfma_chain_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int chain, int blocks, int iters,
+                              double* flop, void* stream) {
+    if (bad_buffers(operands, sink)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (chain != 1 && chain != 2 && chain != 4 && chain != 8) return SKIPARSE_EUNSUPPORTED;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    if (flop) *flop = 2.0 * 32 * 32 * 16 * 4.0 * chain /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
+    return finish(launch_mfma_chain_probe(operands, sink, chain, blocks, iters, (hipStream_t)stream));
 }
 
 int skiparse_lds_read_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int kind, int blocks, int iters,

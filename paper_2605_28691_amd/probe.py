@@ -27,6 +27,8 @@ def lib() -> ctypes.CDLL:
         L.skiparse_mfma_lds_probe.argtypes = [vp, sz, vp, sz, i, i, pd, vp]
         L.skiparse_mfma_valu_probe.restype = i
         L.skiparse_mfma_valu_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
+        L.skiparse_mfma_chain_probe.restype = i
+        L.skiparse_mfma_chain_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
         L.skiparse_lds_read_probe.restype = i
         L.skiparse_lds_read_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
         L.skiparse_probe_device_info.restype = i
@@ -74,6 +76,13 @@ def mfma_valu_probe(operands: torch.Tensor, sink: torch.Tensor, valu_per_mfma: i
     flop = ctypes.c_double(0.0)
     _check(lib().skiparse_mfma_valu_probe(*_args(operands, sink), valu_per_mfma, blocks, iters, ctypes.byref(flop), _stream()),
            "skiparse_mfma_valu_probe")
+    return flop.value
+
+
+def mfma_chain_probe(operands: torch.Tensor, sink: torch.Tensor, chain: int, blocks: int, iters: int) -> float:
+    """bf16 MFMA loop with `chain` consecutive MFMAs on the same accumulator; returns the FLOP of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(lib().skiparse_mfma_chain_probe(*_args(operands, sink), chain, blocks, iters, ctypes.byref(flop), _stream()), "skiparse_mfma_chain_probe")
     return flop.value
 
 
