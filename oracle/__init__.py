@@ -345,3 +345,35 @@ def switch_pattern(y: np.ndarray, T: int, H: int, W: int, s: int, from_pattern: 
     out = np.empty_like(y)
     _check(_load().oracle_switch_pattern(_ptr(y), _ptr(out), B, T, H, W, y.strides[1], s, PATTERNS[from_pattern]), "switch_pattern")
     return out
+
+
+# ---- Sparse Sequence Parallelism (Sec. 3.3; Algorithm 1, sparse_sequence_parallel): the steps of ONE rank, in the paper's order.
+# A rank's shard is [(g, bb)][positions of a subsequence][...]: its G = s*s/group_size subsequences in class order, batch fastest.
+# Plain compositions of this package's permute / unpermute (on the reduced grid (T, H/s, W/s)) and numpy axis moves.
+
+
+def ssp_pack(x: np.ndarray, T: int, H: int, W: int, s: int, group_size: int) -> np.ndarray:
+    """Step 1 and the view of step 2: every held subsequence is split token-wise once more on its own grid (T, H/s, W/s);
+    returns the send buffer [group_size][G][G*b][T*(H/s^2)*(W/s^2)][...] (chunk r goes to rank r)."""
+    G = s * s // group_size
+    if G * group_size != s * s or x.shape[0] % G or H % (s * s) or W % (s * s):
+        raise ValueError("group_size must divide s*s, the shard must hold G subsequences, H and W must be multiples of s*s")
+    y = permute(x, T, H // s, W // s, s, "token")  # [(p' q' B_local)][base][...]
+    return y.reshape((group_size, G, x.shape[0]) + y.shape[1:])
+
+
+def ssp_exchange(sends):
+    """What all_to_all_single does to the ranks' send buffers: rank r receives chunk r of every rank, in rank order."""
+    n = len(sends)
+    return [np.stack([sends[src][dst] for src in range(n)], axis=0) for dst in range(n)]
+
+
+def ssp_unpack(recv: np.ndarray, T: int, H: int, W: int, s: int, group_size: int) -> np.ndarray:
+    """Steps 3 and 4: recv [group_size][G][G*b][base][...] -> view [src rank][g'][g][b], swap the two subsequence axes, flatten to
+    (p q b') order and undo the token-wise split on the reduced grid: the rank's shard in the other pattern's layout."""
+    G = s * s // group_size
+    Bl = recv.shape[2]
+    b = Bl // G
+    r = recv.reshape((group_size, G, G, b) + recv.shape[3:])
+    r = np.ascontiguousarray(np.swapaxes(r, 1, 2)).reshape((s * s * G * b,) + recv.shape[3:])
+    return unpermute(r, T, H // s, W // s, s, "token")
