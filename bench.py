@@ -107,9 +107,9 @@ def main() -> int:
     ap.add_argument("--workload", default="768p", choices=["480p", "768p"])
     ap.add_argument("--cpu-rows", type=int, default=16384, help="query rows the oracle computes for cpu_baseline")
     ap.add_argument("--skip-extras", action="store_true", help="only the headline timing (used under the profiler)")
-    ap.add_argument("--extras", default="probe,group,unfused,permute,chain,bwd,c2,c4,c5,pad,cpu",
+    ap.add_argument("--extras", default="probe,group,unfused,permute,ssp,chain,bwd,c2,c4,c5,pad,cpu",
                     help="comma list of the extra sections to run: probe (MFMA-only kernels: attainable matrix throughput), group, unfused, permute, "
-                         "chain (sparse layout in, other pattern's layout out), bwd (backward pass), c2 (the 480P workload: unfused and fused, "
+                         "ssp (one rank's local rearrangements of Sparse Sequence Parallelism), chain (sparse layout in, other pattern's layout out), bwd (backward pass), c2 (the 480P workload: unfused and fused, "
                          "parity), c4 (hybrid comparison on seed 3: dense, token-wise, group-wise), c5 (8-bit variant, group-wise, seed 4, parity), "
                          "pad (720P-shaped grid in the any-resolution mode), cpu (oracle baseline + parity of the headline)")
     ap.add_argument("--traffic-from", nargs="+", metavar="DIR", help="no benchmark: read rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE output of this "
@@ -304,6 +304,19 @@ def main() -> int:
                 del yg
             del yp
         del ws
+    if "ssp" in sections and "group" in w.patterns:
+        # Sparse Sequence Parallelism (Sec. 3.3), the share of one rank of a group of four (one subsequence each): the local
+        # rearrangements before and after the all-to-all; the exchange itself needs a second GPU and is not part of this build
+        shard = sk.skiparse_permute(qd, T, H, W, s, "token")[2:3].contiguous()
+        send = sk.skiparse_ssp_pack(shard, T, H, W, s, 4)
+        back = torch.empty_like(shard)
+        pk_ms = time_calls(lambda: sk.skiparse_ssp_pack(shard, T, H, W, s, 4, out=send), 20)["avg"]
+        up_ms = time_calls(lambda: sk.skiparse_ssp_unpack(send, T, H, W, s, 4, out=back), 20)["avg"]
+        shard_bytes = shard.numel() * 2
+        extras["ssp_rank_share"] = {"group_size": 4, "shard_MB": round(shard_bytes / 1e6, 1), "pack_ms": round(pk_ms, 4),
+                                    "pack_GBps": round(2 * shard_bytes / pk_ms / 1e6, 1), "unpack_ms": round(up_ms, 4),
+                                    "unpack_GBps": round(2 * shard_bytes / up_ms / 1e6, 1)}
+        del shard, send, back
     if "chain" in sections and "group" in w.patterns:
         # a block of a chain: q, k, v already in the token-wise sparse layout, output written in the group-wise layout
         qs, ks, vs = (sk.skiparse_permute(t, T, H, W, s, "token") for t in (qd, kd, vd))

@@ -65,6 +65,25 @@ int skiparse_switch_pattern(const void* src, void* dst, int B, int heads, int T,
                             int from_pattern, int dtype, void* stream);
 
 /*
+ * The two LOCAL halves of the pattern switch under Sparse Sequence Parallelism (Sec. 3.3; Alg. 1, sparse_sequence_parallel), for the
+ * share of ONE rank.  The s*s subsequences of a sparse layout are spread over group_size ranks, G = s*s/group_size whole subsequences
+ * per rank (group_size must divide s*s; H and W multiples of s*s).  A rank's shard is x[(g, bb)][T*(H/s)*(W/s)][heads][head_dim]:
+ * g in [0, G) its subsequences in class order, bb in [0, b) the batch elements (batch fastest), positions in subsequence order.
+ *   skiparse_ssp_pack    step 1: every held subsequence, a (T, H/s, W/s) grid of its own, is split token-wise once more; the result
+ *                        send[dst rank][g' of dst][(g, bb)][T*(H/(s*s))*(W/(s*s))][heads][head_dim] is the all-to-all's send buffer
+ *                        (chunk `dst rank` goes to that rank; the library performs no communication).
+ *   skiparse_ssp_unpack  steps 3 and 4: recv[src rank][g'][g of src][bb][..] (chunk `src rank` is what that rank sent here) becomes
+ *                        the rank's shard y[(g', bb)][T*(H/s)*(W/s)][..] in the OTHER pattern's sparse layout.  The axis swap
+ *                        of step 3 is folded into the row numbers; one row move per token.
+ * The same pair switches token-wise -> group-wise and group-wise -> token-wise.  group_size = 1 is the single-device switch
+ * (equal to skiparse_switch_pattern).  Bit-exact row moves, any element type; src and dst must not overlap.
+ */
+int skiparse_ssp_pack(const void* x, void* send, int b, int heads, int T, int H, int W, int head_dim, int s, int group_size, int dtype,
+                      void* stream);
+int skiparse_ssp_unpack(const void* recv, void* y, int b, int heads, int T, int H, int W, int head_dim, int s, int group_size, int dtype,
+                        void* stream);
+
+/*
  * Full attention (the dense blocks of the hybrid model, Sec. 3.4; also the per-subsequence step of Sec. 3.1):
  * for every (b, head):  out = softmax(q k^T * scale) v  over all N = T*H*W tokens, no mask, no dropout.
  * q, k, v, out: [B][N][heads][head_dim] bf16 (only N = T*H*W matters).  scale <= 0 selects 1/sqrt(head_dim).

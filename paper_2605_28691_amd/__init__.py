@@ -49,6 +49,10 @@ def lib() -> ctypes.CDLL:
         L.skiparse_unpermute.argtypes = [vp, vp] + [i] * 9 + [vp]
         L.skiparse_switch_pattern.restype = i
         L.skiparse_switch_pattern.argtypes = [vp, vp] + [i] * 9 + [vp]
+        L.skiparse_ssp_pack.restype = i
+        L.skiparse_ssp_pack.argtypes = [vp, vp] + [i] * 9 + [vp]
+        L.skiparse_ssp_unpack.restype = i
+        L.skiparse_ssp_unpack.argtypes = [vp, vp] + [i] * 9 + [vp]
         L.dense_attn_fwd.restype = i
         L.dense_attn_fwd.argtypes = [vp] * 4 + [i] * 6 + [f, i, vp]
         L.skiparse_attn_fwd.restype = i
@@ -141,6 +145,37 @@ def skiparse_switch_pattern(y: torch.Tensor, T: int, H: int, W: int, s: int, fro
     _check(
         lib().skiparse_switch_pattern(_dev(y, "y"), _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[from_pattern], _DTYPES[y.dtype], _stream()),
         "skiparse_switch_pattern",
+    )
+    return out
+
+
+def skiparse_ssp_pack(x: torch.Tensor, T: int, H: int, W: int, s: int, group_size: int, out: torch.Tensor | None = None):
+    """One rank's shard [G*b][T*(H/s)*(W/s)][heads][D] (G = s*s/group_size subsequences, batch fastest) -> the all-to-all send buffer
+    [group_size][G][G*b][T*(H/s^2)*(W/s^2)][heads][D] of Sparse Sequence Parallelism (chunk r is for rank r)."""
+    Bl, n_local, heads, D = x.shape
+    G = (s * s) // group_size
+    if G < 1 or G * group_size != s * s or Bl % G or n_local * s * s != T * H * W:
+        raise ValueError("shard shape does not match the grid and the group")
+    if out is None:
+        out = torch.empty((group_size, G, Bl, n_local // (s * s), heads, D), dtype=x.dtype, device=x.device)
+    _check(
+        lib().skiparse_ssp_pack(_dev(x, "x"), _dev(out, "out"), Bl // G, heads, T, H, W, D, s, group_size, _DTYPES[x.dtype], _stream()),
+        "skiparse_ssp_pack",
+    )
+    return out
+
+
+def skiparse_ssp_unpack(recv: torch.Tensor, T: int, H: int, W: int, s: int, group_size: int, out: torch.Tensor | None = None):
+    """The all-to-all receive buffer [group_size][G][G*b][base][heads][D] (chunk r came from rank r) -> the rank's shard
+    [G*b][T*(H/s)*(W/s)][heads][D] in the other pattern's sparse layout."""
+    gs, G, Bl, base, heads, D = recv.shape
+    if gs != group_size or G * group_size != s * s or Bl % G or base * s * s * s * s != T * H * W:
+        raise ValueError("receive-buffer shape does not match the grid and the group")
+    if out is None:
+        out = torch.empty((Bl, base * s * s, heads, D), dtype=recv.dtype, device=recv.device)
+    _check(
+        lib().skiparse_ssp_unpack(_dev(recv, "recv"), _dev(out, "out"), Bl // G, heads, T, H, W, D, s, group_size, _DTYPES[recv.dtype], _stream()),
+        "skiparse_ssp_unpack",
     )
     return out
 

@@ -153,6 +153,42 @@ int skiparse_unpermute(const void* src, void* dst, int B, int heads, int T, int 
     return permute_common(src, dst, B, heads, T, H, W, head_dim, s, pattern, dtype, stream, 0);
 }
 
+// Local halves of the pattern switch under Sparse Sequence Parallelism (Sec. 3.3; Alg. 1, sparse_sequence_parallel): shared checks.
+static int ssp_common(const void* src, void* dst, int b, int heads, int T, int H, int W, int head_dim, int s, int group_size, int dtype,
+                      void* stream, bool pack) {
+    if (!src || !dst) return SKIPARSE_EINVAL;
+    const int esz = elem_size(dtype);
+    if (esz == 0) return SKIPARSE_EINVAL;
+    if (b < 1 || s < 1 || s > 1024 || group_size < 1) return SKIPARSE_EINVAL;
+    if ((s * s) % group_size != 0) return SKIPARSE_ESHAPE;  // whole subsequences per rank
+    const int G = s * s / group_size;
+    if ((int64_t)G * b > (int64_t)1 << 24) return SKIPARSE_ESHAPE;
+    Shape full;  // the full grid must admit both patterns: H and W multiples of s*s
+    int rc = check_shape(b, heads, T, H, W, head_dim, s, SKIPARSE_GROUP, &full);
+    if (rc != SKIPARSE_OK) return rc;
+    // a rank's shard: G*b batch elements on the reduced grid (T, H/s, W/s), split token-wise once more
+    Shape sh;
+    rc = check_shape(G * b, heads, T, H / s, W / s, head_dim, s, SKIPARSE_TOKEN, &sh);
+    if (rc != SKIPARSE_OK) return rc;
+    if (misaligned(src) || misaligned(dst)) return SKIPARSE_EINVAL;
+    const size_t row_bytes = sh.row_elems * (size_t)esz;
+    if (row_bytes % 16 != 0) return SKIPARSE_EUNSUPPORTED;
+    if (overlap(src, dst, sh.elems * (size_t)esz)) return SKIPARSE_EINVAL;
+    const GridMap g = make_gridmap(T, H / s, W / s, s, SKIPARSE_TOKEN);
+    if (pack) return finish(launch_permute(src, dst, G * b, g, row_bytes, 1, (hipStream_t)stream));
+    return finish(launch_permute(src, dst, G * b, g, row_bytes, 0, (hipStream_t)stream, s == 1 ? 0 : G));
+}
+
+int skiparse_ssp_pack(const void* x, void* send, int b, int heads, int T, int H, int W, int head_dim, int s, int group_size, int dtype,
+                      void* stream) {
+    return ssp_common(x, send, b, heads, T, H, W, head_dim, s, group_size, dtype, stream, true);
+}
+
+int skiparse_ssp_unpack(const void* recv, void* y, int b, int heads, int T, int H, int W, int head_dim, int s, int group_size, int dtype,
+                        void* stream) {
+    return ssp_common(recv, y, b, heads, T, H, W, head_dim, s, group_size, dtype, stream, false);
+}
+
 int skiparse_switch_pattern(const void* src, void* dst, int B, int heads, int T, int H, int W, int head_dim, int s,
                             int from_pattern, int dtype, void* stream) {
     if (!src || !dst) return SKIPARSE_EINVAL;

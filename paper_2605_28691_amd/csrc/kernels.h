@@ -9,9 +9,10 @@
 
 namespace skiparse {
 
-// Row gather/scatter between the original and the sparse layout.  `to_sparse` != 0: dst is sparse.
+// Row gather/scatter between the original and the sparse layout.  `to_sparse` != 0: dst is sparse.  ssp_G > 0: the sparse side is an
+// all-to-all receive buffer of Sparse Sequence Parallelism with ssp_G subsequences per rank (Alg. 1, sparse_sequence_parallel, step 3).
 hipError_t launch_permute(const void* src, void* dst, int B, const GridMap& g, size_t row_bytes, int to_sparse,
-                          hipStream_t stream);
+                          hipStream_t stream, int ssp_G = 0);
 
 // Row moves from the sparse layout of one pattern to that of the other; g_to describes the destination pattern.
 hipError_t launch_switch(const void* src, void* dst, int B, const GridMap& g_to, int from_group, int H, size_t row_bytes,

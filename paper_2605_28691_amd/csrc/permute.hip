@@ -15,22 +15,32 @@ constexpr int PERMUTE_WAVES = 4;  // rows per workgroup
 // and find each token's class and position with the inverse formulas.  Either serves both directions; what differs is which
 // side of the copy is contiguous across wavefronts.  Contiguous WRITES with gathered reads measure faster than the reverse, so
 // the permute (writes the sparse layout) enumerates sparse rows and the unpermute (writes the original layout) original rows.
+// ssp_G > 0 (Sparse Sequence Parallelism, Alg. 1 sparse_sequence_parallel, step 3): the sparse side is a buffer as it arrives from the
+// all-to-all, [source rank][my subsequence g'][source's subsequence g][b][position]; the algorithm's axis swap to
+// [source rank][g][g'][b] = "(p q b')" order is folded into the row number instead of being a pass of its own.
+__device__ inline uint32_t ssp_received_sb(uint32_t sb, uint32_t B, uint32_t G) {
+    const uint32_t b = B / G;                        // batch elements per subsequence
+    const uint32_t pq = sb / B, bi = sb - pq * B;    // class of the source pattern; (g', batch element)
+    const uint32_t r = pq / G, gs = pq - r * G, gd = bi / b, bb = bi - gd * b;
+    return ((r * G + gd) * G + gs) * b + bb;
+}
+
 template <int UNROLL, bool BY_ORIG>
 __global__ __launch_bounds__(PERMUTE_WAVES * 64) void permute_rows_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
                                                                           int B, GridMap g, uint32_t chunks_per_row,
-                                                                          uint32_t n_rows, int to_sparse) {
+                                                                          uint32_t n_rows, int to_sparse, uint32_t ssp_G) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t row = blockIdx.x * PERMUTE_WAVES + (threadIdx.x >> 6);
     if (row >= n_rows) return;
     uint32_t sparse_row, orig_row;
     if (!BY_ORIG) {
         // sparse row -> (sb, j) -> (p, q, b) -> row number in the original layout
-        sparse_row = row;
         const uint32_t n_sub = (uint32_t)g.n_sub;
         const uint32_t sb = row / n_sub, j = row - sb * n_sub;
         const uint32_t pq = sb / (uint32_t)B, b = sb - pq * (uint32_t)B;
         const uint32_t p = pq / (uint32_t)g.s, q = pq - p * (uint32_t)g.s;
         orig_row = b * (uint32_t)g.n_tok + src_token(g, p, q, j);
+        sparse_row = ssp_G ? ssp_received_sb(sb, (uint32_t)B, ssp_G) * n_sub + j : row;
     } else {
         // original row -> (b, t*H + h, w) -> class (p, q) and position (Alg. 1 read backwards; H and W are multiples of s for the
         // token-wise pattern and of s*s for the group-wise one, so t*H + h splits like h)
@@ -52,7 +62,9 @@ __global__ __launch_bounds__(PERMUTE_WAVES * 64) void permute_rows_kernel(const 
                 r = th / s;
                 ws = w / s;
             }
-            sparse_row = ((p * s + q) * (uint32_t)B + b) * (uint32_t)g.n_sub + r * (W / s) + ws;
+            uint32_t sb = (p * s + q) * (uint32_t)B + b;
+            if (ssp_G) sb = ssp_received_sb(sb, (uint32_t)B, ssp_G);
+            sparse_row = sb * (uint32_t)g.n_sub + r * (W / s) + ws;
         }
     }
     const u32x4* s = src + (size_t)(to_sparse ? orig_row : sparse_row) * chunks_per_row;
@@ -132,26 +144,26 @@ hipError_t launch_switch(const void* src, void* dst, int B, const GridMap& g_to,
 
 template <int UNROLL>
 static void launch_rows(const void* src, void* dst, int B, const GridMap& g, uint32_t chunks, uint32_t n_rows, int to_sparse,
-                        hipStream_t stream) {
+                        uint32_t ssp_G, hipStream_t stream) {
     const uint32_t blocks = (n_rows + PERMUTE_WAVES - 1) / PERMUTE_WAVES;
     const bool by_orig = to_sparse ? SKIPARSE_PERMUTE_BY_ORIG : SKIPARSE_UNPERMUTE_BY_ORIG;
     if (by_orig)
-        permute_rows_kernel<UNROLL, true><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+        permute_rows_kernel<UNROLL, true><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse, ssp_G);
     else
-        permute_rows_kernel<UNROLL, false><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse);
+        permute_rows_kernel<UNROLL, false><<<blocks, PERMUTE_WAVES * 64, 0, stream>>>((const u32x4*)src, (u32x4*)dst, B, g, chunks, n_rows, to_sparse, ssp_G);
 }
 
 hipError_t launch_permute(const void* src, void* dst, int B, const GridMap& g, size_t row_bytes, int to_sparse,
-                          hipStream_t stream) {
+                          hipStream_t stream, int ssp_G) {
     const uint32_t chunks = (uint32_t)(row_bytes / 16);
     const uint32_t s2 = g.mode == MODE_DENSE ? 1u : (uint32_t)(g.s * g.s);
     const uint32_t n_rows = (uint32_t)B * s2 * (uint32_t)g.n_sub;
     if (chunks >= 5 * 64)
-        launch_rows<5>(src, dst, B, g, chunks, n_rows, to_sparse, stream);
+        launch_rows<5>(src, dst, B, g, chunks, n_rows, to_sparse, (uint32_t)ssp_G, stream);
     else if (chunks >= 3 * 64)
-        launch_rows<3>(src, dst, B, g, chunks, n_rows, to_sparse, stream);
+        launch_rows<3>(src, dst, B, g, chunks, n_rows, to_sparse, (uint32_t)ssp_G, stream);
     else
-        launch_rows<1>(src, dst, B, g, chunks, n_rows, to_sparse, stream);
+        launch_rows<1>(src, dst, B, g, chunks, n_rows, to_sparse, (uint32_t)ssp_G, stream);
     return hipGetLastError();
 }
 

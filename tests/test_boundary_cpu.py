@@ -47,7 +47,7 @@ def test_every_declared_symbol_is_exported(lib):
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
             "skiparse_switch_pattern", "skiparse_attn_fwd_sparse", "skiparse_attn_fwd_lse",
             "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes", "skiparse_attn_bwd_static",
-            "skiparse_static_scratch_bytes"} <= set(names)
+            "skiparse_static_scratch_bytes", "skiparse_ssp_pack", "skiparse_ssp_unpack"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert not [n for n in names if "probe" in n]  # the measurement kernels live in a library of their own
@@ -242,3 +242,17 @@ def test_static_scratch_backward_rejects_what_does_not_fit(lib):
     assert lib.skiparse_attn_bwd_static(*ptrs, 1, 2, 2, 8, 6, 64, 2, 1, f, 0, 0, None) == -2   # group-wise needs W % 4 == 0
     assert lib.skiparse_attn_bwd_static(*ptrs, 1, 2, 2, 8, 8, 96, 2, 0, f, 0, 0, None) == -3   # head_dim 96
     assert lib.skiparse_attn_bwd_static(*ptrs, 1, 2, 2, 8, 8, 64, 2, 0, f, 0, 4, None) == -1   # unknown flag
+
+
+def test_ssp_entry_points_reject_bad_arguments(lib):
+    p, q = ctypes.c_void_p(FAKE), ctypes.c_void_p(FAKE + (1 << 30))
+    for fn in (lib.skiparse_ssp_pack, lib.skiparse_ssp_unpack):
+        ok = [1, 2, 2, 8, 8, 64, 2, 2, 0]  # b, heads, T, H, W, head_dim, s, group_size, dtype
+        assert fn(None, q, *ok, None) == -1
+        assert fn(p, p, *ok, None) == -1                                    # src == dst
+        assert fn(p, q, 1, 2, 2, 8, 8, 64, 2, 3, 0, None) == -2             # group_size must divide s*s
+        assert fn(p, q, 1, 2, 2, 8, 6, 64, 2, 2, 0, None) == -2             # W must be a multiple of s*s
+        assert fn(p, q, 0, 2, 2, 8, 8, 64, 2, 2, 0, None) == -1
+        assert fn(p, q, 1, 2, 2, 8, 8, 64, 2, 0, 0, None) == -1
+        assert fn(p, q, 1, 2, 2, 8, 8, 64, 2, 2, 7, None) == -1             # unknown element type
+        assert fn(ctypes.c_void_p(FAKE + 8), q, *ok, None) == -1            # misaligned
