@@ -234,3 +234,33 @@ def test_fused_equals_unfused_bit_for_bit_on_random_shapes():
         b = sk.skiparse_attn_fwd(q, k, v, T, H, W, s, pattern, scale=w.scale, fused=False)
         assert torch.equal(a, b), (case, B, heads, D, T, H, W, s, pattern)
         assert bool(torch.isfinite(a.float()).all())
+
+
+def test_largest_admitted_batch_element_sampled_rows():
+    """Maximum size: one batch element just below the 4 GiB that the kernels' 32-bit row offsets can address (40 heads of 128,
+    grid 21 x 120 x 166 = 418,320 tokens: 4,283,596,800 bytes per tensor, 99.7 % of the limit; subsequences of 104,580 tokens with a
+    ragged last tile).  Sampled query rows against the oracle, among them the first and the very last token (the highest offset), and
+    canaries behind the output.  One token row more per batch element is rejected by the size check."""
+    import ctypes
+
+    import paper_2605_28691_amd as sk
+
+    B, heads, D, T, H, W, s = 1, 40, 128, 21, 120, 166, 2
+    N = T * H * W
+    assert N * heads * D * 2 < 2 ** 32 <= T * 120 * 168 * heads * D * 2
+    g = torch.Generator(device="cuda").manual_seed(77)
+    q, k, v = (torch.randn((B, N, heads, D), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+    buf = torch.full((q.numel() + 4096,), 3.0, dtype=torch.bfloat16, device="cuda")
+    out = buf[:q.numel()].view_as(q)
+    sk.skiparse_attn_fwd(q, k, v, T, H, W, s, "token", fused=True, out=out)
+    torch.cuda.synchronize()
+    assert bool((buf[q.numel():] == 3.0).all())
+    rng = np.random.default_rng(5)
+    rows = np.array([(0, int(h), int(n)) for h, n in zip(rng.integers(0, heads, 60), rng.integers(0, N, 60))]
+                    + [(0, 0, 0), (0, heads - 1, N - 1), (0, 17, N - 1), (0, 3, N - 2)], dtype=np.int64)
+    want = oracle.skiparse_attention_rows(*(si.as_oracle_array(t.cpu()) for t in (q, k, v)), rows, T, H, W, s, "token", 1.0 / np.sqrt(D))
+    assert_close_bf16(gather_rows(out, rows), want, "largest batch element")
+    # 21 x 120 x 167 tokens would pass 4 GiB: refused before anything is launched
+    p = [ctypes.c_void_p(t.data_ptr()) for t in (q, k, v, out)]
+    rc = sk.lib().skiparse_attn_fwd(*p, 1, heads, T, 120, 168, D, s, 0, ctypes.c_float(0.0), 0, 1, None, 0, None)
+    assert rc == -2
