@@ -75,3 +75,23 @@ def test_768p_token_to_group_sampled_rows():
         p, qq, j = oracle.dst_index("group", w.s, w.T, w.H, w.W, int(n))
         got[i] = to_np64(out[(p * w.s + qq) * w.B + int(b), j, int(head)])
     assert_close_bf16(got, want, "768p token -> group")
+
+
+def test_calls_follow_the_current_stream():
+    """The binding hands torch's CURRENT stream to the library: a call issued on a side stream, ordered after the producer of its
+    inputs by stream semantics alone, gives the same bits as the call on the default stream."""
+    import paper_2605_28691_amd as sk
+
+    B, heads, D, T, H, W, s = 1, 4, 128, 6, 16, 16, 2
+    w = si.make_shape("stream", B, heads, D, T, H, W, s, seed=19)
+    q, k, v = (t.cuda() for t in si.make_qkv(w))
+    want = sk.skiparse_attn_fwd(q, k, v, T, H, W, s, "token", fused=True)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()  # default priority
+    with torch.cuda.stream(side):
+        q2 = q * 1.0  # produced on the side stream; the attention call below must run after it on the same stream
+        got = sk.skiparse_attn_fwd(q2, k, v, T, H, W, s, "token", fused=True)
+        y = sk.skiparse_permute(got, T, H, W, s, "group")
+    side.synchronize()
+    assert torch.equal(got, want)
+    assert torch.equal(sk.skiparse_unpermute(y, T, H, W, s, "group"), want)
