@@ -467,6 +467,25 @@ def main() -> int:
         if not (par5["max_abs"] <= 6e-2 and par5["rel_l2"] <= 8e-2):  # the format's floor with margin; the stated 2e-2 is reported above
             failures.append("config5_fp8 parity backstop")
         del q5d, k5d, v5d, q8, k8, v8
+    # the other kernels against the roofline that bounds each (same form as the headline's object; figures from the sections above)
+    others = {}
+    if "permute_GBps" in extras:
+        others["permute_rows_kernel (permute)"] = {"bound": "hbm", "achieved": extras["permute_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                   "frac": round(extras["permute_GBps"] / PEAK_HBM_GBS, 4)}
+        others["permute_rows_kernel (unpermute)"] = {"bound": "hbm", "achieved": extras["unpermute_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                     "frac": round(extras["unpermute_GBps"] / PEAK_HBM_GBS, 4)}
+    if "config5_fp8" in extras:
+        c5 = extras["config5_fp8"]
+        others["quantize_fp8_kernel"] = {"bound": "hbm", "achieved": c5["quantize_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                         "frac": round(c5["quantize_GBps"] / PEAK_HBM_GBS, 4)}
+        others["attn_fwd_fp8_kernel"] = {"bound": "mfma", "achieved": c5["attn_tflops"], "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
+                                         "frac": c5["frac_of_fp8_mfma_peak"]}
+    if "bwd_ms" in extras:
+        others["attn_bwd_kernel (dQ + dK,dV launches, 7 products executed)"] = {
+            "bound": "mfma", "achieved": extras["bwd_executed_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(extras["bwd_executed_tflops"] / PEAK_BF16_TFLOPS, 4), "frac_on_the_5_product_definition": extras["bwd_frac_of_bf16_peak_effective"]}
+    if others:
+        extras["rooflines_of_the_other_kernels"] = others
     if extras:
         result["extras"] = extras
 
