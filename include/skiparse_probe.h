@@ -43,6 +43,10 @@ int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* 
 int skiparse_mfma_lds_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int blocks, int iters, double* flop,
                             void* stream);
 
+/* The same with the 8-bit instruction (32x32x64 fp8, iters * 2 per wavefront) and valu_per_mfma in {0, 4, 8, 12, 16}. */
+int skiparse_mfma8_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
+                              int iters, double* flop, void* stream);
+
 /*
  * The bf16 loop with `chain` (1, 2, 4 or 8) consecutive MFMAs on the same accumulator before moving to the next of four
  * (iters * 4 * chain instructions per wavefront): whether accumulator reuse inside the matrix pipe changes its sustained rate.

@@ -138,6 +138,50 @@ __global__ __launch_bounds__(PROBE_THREADS) void mfma_valu_probe_kernel(const ch
     sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
 }
 
+// The same for the 8-bit matrix instruction (32x32x64, 64 clocks): NV independent v_fma_f32 after every MFMA.
+template <int NV>
+__global__ __launch_bounds__(PROBE_THREADS) void mfma8_valu_probe_kernel(const char* __restrict__ operands, float* __restrict__ sink, int iters) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const i32x8 av = *(const i32x8*)(operands + (size_t)lane * 32), bv = *(const i32x8*)(operands + ((size_t)64 + lane) * 32);
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+        acc0[r] = 0.f;
+        acc1[r] = 0.f;
+    }
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = (float)(lane + i) * 1e-3f;
+    const float c = 0.999f;
+    for (int it = 0; it < iters; it++) {
+        acc0 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc0, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NV; i++) v[i % 16] = fmaf(v[i % 16], c, c);
+        __builtin_amdgcn_sched_barrier(0);
+        acc1 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bv, av, acc1, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NV; i++) v[(i + 8) % 16] = fmaf(v[(i + 8) % 16], c, c);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r++) s += acc0[r] + acc1[r] + v[r];
+    sink[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
+}
+
+static hipError_t launch_mfma8_valu_probe(const void* operands, float* sink, int valu_per_mfma, int blocks, int iters, hipStream_t stream) {
+    const char* ops = (const char*)operands;
+    switch (valu_per_mfma) {
+        case 0: mfma8_valu_probe_kernel<0><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        case 4: mfma8_valu_probe_kernel<4><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        case 8: mfma8_valu_probe_kernel<8><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        case 12: mfma8_valu_probe_kernel<12><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        case 16: mfma8_valu_probe_kernel<16><<<blocks, PROBE_THREADS, 0, stream>>>(ops, sink, iters); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // Third probe: the bf16 MFMA loop with the A operand of EVERY MFMA read from LDS (ds_read_b128, 32 KiB of the caller's operands walked
 // in 8 KiB steps), as an attention kernel has to feed its matrix products; B operands cycle through 8 register fragments.
 __global__ __launch_bounds__(PROBE_THREADS) void mfma_lds_probe_kernel(const char* __restrict__ operands, float* __restrict__ sink, int iters) {
@@ -310,6 +354,16 @@ int skiparse_mfma_valu_probe(const void* operands, size_t operand_bytes, float* 
     if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
     if (flop) *flop = 2.0 * 32 * 32 * 16 * 2.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
     return finish(launch_mfma_valu_probe(operands, sink, valu_per_mfma, blocks, iters, (hipStream_t)stream));
+}
+
+int skiparse_mfma8_valu_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int valu_per_mfma, int blocks,
+                              int iters, double* flop, void* stream) {
+    if (bad_buffers(operands, sink)) return SKIPARSE_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return SKIPARSE_EINVAL;
+    if (valu_per_mfma < 0 || valu_per_mfma > 16 || (valu_per_mfma & 3)) return SKIPARSE_EUNSUPPORTED;
+    if (operand_bytes < (size_t)MFMA_PROBE_OPERAND_BYTES || sink_bytes < (size_t)blocks * 256 * sizeof(float)) return SKIPARSE_EWORKSPACE;
+    if (flop) *flop = 2.0 * 32 * 32 * 64 * 2.0 /* MFMAs per iteration */ * iters * 4.0 /* wavefronts */ * blocks;
+    return finish(launch_mfma8_valu_probe(operands, sink, valu_per_mfma, blocks, iters, (hipStream_t)stream));
 }
 
 int skiparse_mfma_chain_probe(const void* operands, size_t operand_bytes, float* sink, size_t sink_bytes, int chain, int blocks, int iters,

@@ -27,6 +27,8 @@ def lib() -> ctypes.CDLL:
         L.skiparse_mfma_lds_probe.argtypes = [vp, sz, vp, sz, i, i, pd, vp]
         L.skiparse_mfma_valu_probe.restype = i
         L.skiparse_mfma_valu_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
+        L.skiparse_mfma8_valu_probe.restype = i
+        L.skiparse_mfma8_valu_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
         L.skiparse_mfma_chain_probe.restype = i
         L.skiparse_mfma_chain_probe.argtypes = [vp, sz, vp, sz, i, i, i, pd, vp]
         L.skiparse_lds_read_probe.restype = i
@@ -76,6 +78,14 @@ def mfma_valu_probe(operands: torch.Tensor, sink: torch.Tensor, valu_per_mfma: i
     flop = ctypes.c_double(0.0)
     _check(lib().skiparse_mfma_valu_probe(*_args(operands, sink), valu_per_mfma, blocks, iters, ctypes.byref(flop), _stream()),
            "skiparse_mfma_valu_probe")
+    return flop.value
+
+
+def mfma8_valu_probe(operands: torch.Tensor, sink: torch.Tensor, valu_per_mfma: int, blocks: int, iters: int) -> float:
+    """fp8 MFMA loop with `valu_per_mfma` independent FMAs after every MFMA; returns the FLOP of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(lib().skiparse_mfma8_valu_probe(*_args(operands, sink), valu_per_mfma, blocks, iters, ctypes.byref(flop), _stream()),
+           "skiparse_mfma8_valu_probe")
     return flop.value
 
 

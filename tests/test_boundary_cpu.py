@@ -55,7 +55,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_every_declared_probe_symbol_is_exported(probe_lib):
     names = _declared_functions(PROBE_HEADER)
-    assert {"skiparse_mfma_probe", "skiparse_mfma_valu_probe", "skiparse_mfma_lds_probe", "skiparse_lds_read_probe", "skiparse_probe_device_info",
+    assert {"skiparse_mfma_probe", "skiparse_mfma_valu_probe", "skiparse_mfma_lds_probe", "skiparse_lds_read_probe", "skiparse_mfma_chain_probe", "skiparse_mfma8_valu_probe", "skiparse_probe_device_info",
             "skiparse_probe_last_hip_error"} <= set(names)
     for n in names:
         assert hasattr(probe_lib, n), n
@@ -225,6 +225,8 @@ def test_mfma_probe_rejects_bad_arguments(probe_lib):
     assert lib.skiparse_lds_read_probe(p, 1 << 20, q, 1 << 30, 3, 8, 10, ctypes.byref(flop), None) == -3    # kinds 0..2
     assert lib.skiparse_lds_read_probe(p, 1 << 20, q, 8 * 512 * 4 - 1, 0, 8, 10, ctypes.byref(flop), None) == -4
     assert lib.skiparse_lds_read_probe(None, 1 << 20, q, 1 << 30, 0, 8, 10, ctypes.byref(flop), None) == -1
+    assert lib.skiparse_mfma8_valu_probe(p, 1 << 20, q, 1 << 30, 6, 8, 10, ctypes.byref(flop), None) == -3   # multiples of 4 up to 16
+    assert lib.skiparse_mfma_chain_probe(p, 1 << 20, q, 1 << 30, 3, 8, 10, ctypes.byref(flop), None) == -3   # 1, 2, 4 or 8
     assert lib.skiparse_probe_device_info(0, None, None) == -1
     assert lib.skiparse_probe_device_info(-1, ctypes.byref(ctypes.c_int()), ctypes.byref(ctypes.c_int())) == -1
 

@@ -66,3 +66,16 @@ def test_lds_read_probe_runs_and_counts_bytes():
         assert nbytes == per_read * 16 * 3 * 8 * 4
     torch.cuda.synchronize()
     assert bool(torch.isfinite(sink).all()) and bool((sink >= 0).all())
+
+
+def test_mfma8_valu_probe_runs():
+    from paper_2605_28691_amd import probe
+
+    ops = torch.zeros(16384, dtype=torch.uint8, device="cuda")
+    sink = torch.full((8 * 256,), -1.0, dtype=torch.float32, device="cuda")
+    for n in (0, 4, 8, 12, 16):
+        assert probe.mfma8_valu_probe(ops, sink, n, 8, 5) == 2.0 * 32 * 32 * 64 * 2 * 5 * 4 * 8
+    for chain in (1, 2, 4, 8):
+        assert probe.mfma_chain_probe(ops.view(torch.bfloat16), sink, chain, 8, 5) == 2.0 * 32 * 32 * 16 * 4 * chain * 5 * 4 * 8
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
