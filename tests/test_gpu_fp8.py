@@ -43,6 +43,7 @@ CASES = [  # B, heads, D, T, H, W, s
     (1, 2, 128, 9, 16, 16, 2),   # Nsub = 576 = 4.5 blocks
     (1, 5, 128, 4, 9, 18, 3),    # s = 3
     (1, 2, 64, 11, 16, 16, 4),   # s = 4, head_dim 64, Nsub = 176
+    (1, 2, 128, 3, 8, 16, 1),    # s = 1: 8-bit FULL attention (the hybrid model's dense blocks), 384 tokens = 3 scale blocks
 ]
 
 
