@@ -327,8 +327,12 @@ __global__ __launch_bounds__(BNT) void attn_bwd_kernel(BwdArgs a, uint32_t o_til
             auto frag_c = [&](int cidx) __attribute__((always_inline)) -> bf16x8 {
                 const int pair = DKV ? cidx / 2 : cidx, g2 = pair / MT, mt = pair % MT;
                 const char* ta = ((DKV && cidx % 2 == 1) ? t2 : t1) + (blk * 32 + g2 * 16) * RB;  // dV reads the dO tile, dQ and dK the first tensor
-                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[0][mt]));
-                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + t_rd[1][mt]));
+                // the offset of channel block mt is that of block 0 with mt * 64 XORed in (the swizzle moves only bits 4-7, and the
+                // block number enters through bits 6-7): the dK+dV launch keeps two registers instead of the table
+                const uint32_t o0 = ADDR_TABLE ? t_rd[0][mt] : (t_rd[0][0] ^ (uint32_t)(mt * 64));
+                const uint32_t o1 = ADDR_TABLE ? t_rd[1][mt] : (t_rd[1][0] ^ (uint32_t)(mt * 64));
+                const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + o0));
+                const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(LDS_PTR(char))(ta + o1));
                 return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
             };
             bf16x8 fc[NC];
