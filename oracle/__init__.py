@@ -377,3 +377,20 @@ def ssp_unpack(recv: np.ndarray, T: int, H: int, W: int, s: int, group_size: int
     r = recv.reshape((group_size, G, G, b) + recv.shape[3:])
     r = np.ascontiguousarray(np.swapaxes(r, 1, 2)).reshape((s * s * G * b,) + recv.shape[3:])
     return unpermute(r, T, H // s, W // s, s, "token")
+
+
+def quantize_fp8_padded(x: np.ndarray, T: int, H: int, W: int, s: int, pattern: str):
+    """The 8-bit workload's quantiser in the any-resolution mode (Sec. 3.2): the grid is padded with zero tokens at the END of H and W
+    to the next multiples of s*s and the padded tensor is quantised as usual.  Zero rows do not move a block's maximum and encode to
+    code 0, so padding positions hold zeros and every scale is that of the block's real rows (1 for a block of nothing but padding).
+    Returns (codes [s*s*B][T*Hp*Wp/s^2][heads][D], scales [s*s*B][heads][ceil(Nsub_padded/128)])."""
+    if x.dtype != np.uint16:
+        raise ValueError("quantize_fp8_padded takes uint16 bf16 bit patterns")
+    B, N, heads, D = x.shape
+    if N != T * H * W:
+        raise ValueError("token axis does not match T*H*W")
+    u = s * s
+    Hp, Wp = (H + u - 1) // u * u, (W + u - 1) // u * u
+    g = x.reshape(B, T, H, W, heads, D)
+    g = np.pad(g, ((0, 0), (0, 0), (0, Hp - H), (0, Wp - W), (0, 0), (0, 0)))  # bf16 bit pattern 0 is +0.0
+    return quantize_fp8(np.ascontiguousarray(g.reshape(B, T * Hp * Wp, heads, D)), T, Hp, Wp, s, pattern)

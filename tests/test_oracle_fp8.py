@@ -64,3 +64,36 @@ def test_quantize_two_blocks_and_zero_block():
     assert scales.shape == (4, 1, 2)
     assert scales[0, 0, 1] == 1.0 and (x8[0, 128:, 0] & 0x7F == 0).all()
     assert scales[0, 0, 0] > 0 and scales[1, 0, 1] != 1.0
+
+
+@pytest.mark.parametrize("pattern", ["token", "group"])
+def test_padded_quantiser_places_zeros_at_padding_and_ignores_them_in_the_scales(pattern):
+    """Any-resolution mode: a 3 x 3 grid with s = 2 is padded to 4 x 4.  In the hand-worked 4 x 4 table (tests/golden) the token-wise
+    class (1, 1) holds (h, w) = (1,1), (1,3), (3,1), (3,3) and the group-wise class (1, 1) holds (2,2), (2,3), (3,2), (3,3): one real
+    token followed by three padding positions in both."""
+    B, heads, D, T, H, W, s = 1, 2, 8, 2, 3, 3, 2
+    w = si.make_shape("qp", B, heads, D, T, H, W, s, seed=6)
+    x = si.make_qkv(w)[0]
+    x8, sc = oracle.quantize_fp8_padded(si.as_oracle_array(x), T, H, W, s, pattern)
+    assert x8.shape == (4, T * 4, heads, D) and sc.shape == (4, heads, 1)
+    real_hw = (1, 1) if pattern == "token" else (2, 2)
+    xf = x.float().numpy().reshape(B, T, H, W, heads, D)
+    for t in range(T):
+        rows = x8[3, 4 * t:4 * t + 4]                       # class (1, 1), frame t: 4 positions
+        assert not rows[1:].any()                           # padding positions: code 0
+        amax = np.abs(xf[0, :, real_hw[0], real_hw[1]]).max(axis=(0, 2))   # over the class's real tokens (all frames) and channels
+        for hd in range(heads):
+            assert sc[3, hd, 0] == np.float32(amax[hd]) / np.float32(448.0)
+            want = [oracle.e4m3_encode(float(np.float32(v) * (np.float32(448.0) / np.float32(amax[hd])))) for v in xf[0, t, real_hw[0], real_hw[1], hd]]
+            assert [c & 0xFF for c in rows[0, hd]] == want or all((a & 0x7F) == 0 and (b & 0x7F) == 0 or a == b for a, b in zip(rows[0, hd], want))
+    # a divisible grid: the padded quantiser is the plain one
+    w2 = si.make_shape("qd", 2, 2, 16, 3, 8, 8, 2, seed=7)
+    x2 = si.as_oracle_array(si.make_qkv(w2)[0])
+    a8, a_s = oracle.quantize_fp8_padded(x2, 3, 8, 8, 2, pattern)
+    b8, b_s = oracle.quantize_fp8(x2, 3, 8, 8, 2, pattern)
+    assert np.array_equal(a8, b8) and np.array_equal(a_s, b_s)
+    # H = 1 with s = 2, token-wise: the classes with p = 1 hold padding only: scale 1, all codes 0
+    if pattern == "token":
+        w3 = si.make_shape("q1", 1, 1, 8, 2, 1, 8, 2, seed=8)
+        c8, c_s = oracle.quantize_fp8_padded(si.as_oracle_array(si.make_qkv(w3)[0]), 2, 1, 8, 2, "token")
+        assert not c8[2:].any() and (c_s[2:] == 1.0).all()
