@@ -359,6 +359,13 @@ def main() -> int:
                 real_flops += 4.0 * w.B * w.heads * float(n_c) ** 2 * w.D
         extras["pad720p_token_ms"] = round(pad_ms, 4)
         extras["pad720p_real_tflops"] = round(real_flops / pad_ms / 1e9, 2)
+        # the 8-bit variant on the same padded workload (the paper reports its 8-bit numbers at 720 x 1280 too)
+        pq8 = [sk.skiparse_quantize_fp8(t, T, Hp_real, W, s, "token", pad=True) for t in (qp, kp, vp)]
+        p8_ms = time_calls(lambda: sk.skiparse_attn_fwd_fp8(pq8[0][0], pq8[1][0], pq8[2][0], pq8[0][1], pq8[1][1], pq8[2][1], T, Hp_real, W, s, "token",
+                                                            scale=w.scale, out=op, pad=True), it)["avg"]
+        extras["pad720p_fp8_token_ms"] = round(p8_ms, 4)
+        extras["pad720p_fp8_real_tflops"] = round(real_flops / p8_ms / 1e9, 2)
+        del pq8
         if "bwd" in sections:
             # the paper's training grid (Sec. 4.1): backward in the any-resolution mode
             dop = torch.randn(shp, generator=g, device="cuda", dtype=torch.bfloat16)

@@ -190,6 +190,20 @@ int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const 
                           void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
                           float scale, void* stream);
 
+/*
+ * The same two calls with a flags argument: 0, or SKIPARSE_PAD for the any-resolution mode (Sec. 3.2; the paper reports its 8-bit
+ * numbers on the padded 720x1280 workload as well).  With SKIPARSE_PAD, H and W are arbitrary; positions run over the grid padded at
+ * the END of H and W to multiples of s*s: x8 is [s*s*B][T*Hp*Wp/(s*s)][heads][head_dim] with zero codes at the padding positions,
+ * scales [s*s*B][heads][ceil(positions/128)] (a block's scale is taken over its real rows; 1 for a block of nothing but padding);
+ * the attention masks the padding positions as keys, skips them as queries and writes only the T*H*W real rows of out_bf16.
+ * skiparse_lse_bytes(..., SKIPARSE_PAD) / (4 * s*s*B*heads) gives the positions per subsequence.
+ */
+int skiparse_quantize_fp8_ex(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
+                             int s, int pattern, unsigned flags, void* stream);
+int skiparse_attn_fwd_fp8_ex(const void* q8, const void* k8, const void* v8, const float* sq, const float* sk, const float* sv,
+                             void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                             float scale, unsigned flags, void* stream);
+
 /* Text for an error code; never NULL. */
 const char* skiparse_strerror(int code);
 

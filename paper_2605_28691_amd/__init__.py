@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.skiparse_static_scratch_bytes.argtypes = []
         L.skiparse_workspace_bytes.restype = sz
         L.skiparse_workspace_bytes.argtypes = [i] * 8 + [u]
+        L.skiparse_quantize_fp8_ex.restype = i
+        L.skiparse_quantize_fp8_ex.argtypes = [vp, vp, vp] + [i] * 8 + [u, vp]
+        L.skiparse_attn_fwd_fp8_ex.restype = i
+        L.skiparse_attn_fwd_fp8_ex.argtypes = [vp] * 7 + [i] * 8 + [f, u, vp]
         L.skiparse_quantize_fp8.restype = i
         L.skiparse_quantize_fp8.argtypes = [vp, vp, vp] + [i] * 8 + [vp]
         L.skiparse_attn_fwd_fp8.restype = i
@@ -301,36 +305,37 @@ def skiparse_attn_bwd_static(q, k, v, out, dout, lse, dq, dk, dv, T: int, H: int
     return dq, dk, dv
 
 
-def skiparse_quantize_fp8(x: torch.Tensor, T: int, H: int, W: int, s: int, pattern: str):
-    """bf16 [B][N][heads][D] (original layout) -> (uint8 E4M3 codes [s*s*B][N/s^2][heads][D] in the sparse layout,
-    float32 scales [s*s*B][heads][ceil(Nsub/128)])."""
+def skiparse_quantize_fp8(x: torch.Tensor, T: int, H: int, W: int, s: int, pattern: str, pad: bool = False):
+    """bf16 [B][N][heads][D] (original layout) -> (uint8 E4M3 codes [s*s*B][positions][heads][D] in the sparse layout,
+    float32 scales [s*s*B][heads][ceil(positions/128)]).  positions = N/s^2, or with pad=True (any-resolution mode) the positions
+    of the grid padded to multiples of s*s, with zero codes at the padding."""
     B, heads, D = _dims(x, T, H, W)
     if x.dtype != torch.bfloat16:
         raise ValueError("skiparse_quantize_fp8 takes bf16 input")
-    nsub = (T * H * W) // (s * s)
+    nsub = skiparse_lse_shape(B, heads, T, H, W, D, s, pattern, pad)[2]
     x8 = torch.empty((s * s * B, nsub, heads, D), dtype=torch.uint8, device=x.device)
     scales = torch.empty((s * s * B, heads, (nsub + 127) // 128), dtype=torch.float32, device=x.device)
     _check(
-        lib().skiparse_quantize_fp8(_dev(x, "x"), _dev(x8, "x8"), _dev(scales, "scales"), B, heads, T, H, W, D, s,
-                                    PATTERNS[pattern], _stream()),
+        lib().skiparse_quantize_fp8_ex(_dev(x, "x"), _dev(x8, "x8"), _dev(scales, "scales"), B, heads, T, H, W, D, s,
+                                       PATTERNS[pattern], PAD if pad else 0, _stream()),
         "skiparse_quantize_fp8",
     )
     return x8, scales
 
 
 def skiparse_attn_fwd_fp8(q8, k8, v8, sq, sk, sv, T: int, H: int, W: int, s: int, pattern: str, scale: float = 0.0,
-                          out: torch.Tensor | None = None):
-    """Attention on quantised sparse-layout tensors (from skiparse_quantize_fp8); bf16 output [B][N][heads][D] in the
+                          out: torch.Tensor | None = None, pad: bool = False):
+    """Attention on quantised sparse-layout tensors (from skiparse_quantize_fp8, same pad flag); bf16 output [B][N][heads][D] in the
     original layout."""
     SB, nsub, heads, D = q8.shape
     B = SB // (s * s)
-    if SB != B * s * s or nsub * s * s != T * H * W:
+    if SB != B * s * s or (not pad and nsub * s * s != T * H * W):
         raise ValueError("sparse-layout shape does not match the grid")
     if out is None:
         out = torch.empty((B, T * H * W, heads, D), dtype=torch.bfloat16, device=q8.device)
     _check(
-        lib().skiparse_attn_fwd_fp8(_dev(q8, "q8"), _dev(k8, "k8"), _dev(v8, "v8"), _dev(sq, "sq"), _dev(sk, "sk"), _dev(sv, "sv"),
-                                    _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), _stream()),
+        lib().skiparse_attn_fwd_fp8_ex(_dev(q8, "q8"), _dev(k8, "k8"), _dev(v8, "v8"), _dev(sq, "sq"), _dev(sk, "sk"), _dev(sv, "sv"),
+                                       _dev(out, "out"), B, heads, T, H, W, D, s, PATTERNS[pattern], float(scale), PAD if pad else 0, _stream()),
         "skiparse_attn_fwd_fp8",
     )
     return out

@@ -431,44 +431,66 @@ int skiparse_attn_bwd_static(const void* q, const void* k, const void* v, const 
                            true, stream);
 }
 
-int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
-                          int s, int pattern, void* stream) {
+// elements of a tensor in the sparse layout over the (possibly padded) grid: s*s*B subsequences of sh.n_sub positions
+static size_t sparse_elems(int B, int s, const Shape& sh) { return (size_t)s * s * B * sh.n_sub * sh.row_elems; }
+
+int skiparse_quantize_fp8_ex(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
+                             int s, int pattern, unsigned flags, void* stream) {
+    if (flags & ~(unsigned)SKIPARSE_PAD) return SKIPARSE_EINVAL;
+    const bool pad = (flags & SKIPARSE_PAD) != 0 && s > 1;
     Shape sh;
-    const int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    const int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh, pad);
     if (rc != SKIPARSE_OK) return rc;
     if (!x_bf16 || !x8 || !scales) return SKIPARSE_EINVAL;
     if (misaligned(x_bf16) || misaligned(x8) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return SKIPARSE_EINVAL;
     if (head_dim != 64 && head_dim != 128) return SKIPARSE_EUNSUPPORTED;
-    if (overlap2(x_bf16, sh.elems * 2, x8, sh.elems)) return SKIPARSE_EINVAL;
-    const GridMap g = make_gridmap(T, H, W, s, pattern);
-    return finish(launch_quantize_fp8(x_bf16, x8, scales, B, heads, head_dim, g, (hipStream_t)stream));
+    if (overlap2(x_bf16, sh.elems * 2, x8, sparse_elems(B, s, sh))) return SKIPARSE_EINVAL;
+    const GridMap g = make_gridmap(T, H, W, s, pattern, pad);
+    return finish(launch_quantize_fp8(x_bf16, x8, scales, B, heads, head_dim, g, pad, (hipStream_t)stream));
 }
 
-int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* sq, const float* sk, const float* sv,
-                          void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
-                          float scale, void* stream) {
+int skiparse_quantize_fp8(const void* x_bf16, void* x8, float* scales, int B, int heads, int T, int H, int W, int head_dim,
+                          int s, int pattern, void* stream) {
+    return skiparse_quantize_fp8_ex(x_bf16, x8, scales, B, heads, T, H, W, head_dim, s, pattern, 0u, stream);
+}
+
+int skiparse_attn_fwd_fp8_ex(const void* q8, const void* k8, const void* v8, const float* sq, const float* sk, const float* sv,
+                             void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                             float scale, unsigned flags, void* stream) {
+    if (flags & ~(unsigned)SKIPARSE_PAD) return SKIPARSE_EINVAL;
+    const bool pad = (flags & SKIPARSE_PAD) != 0 && s > 1;
     Shape sh;
-    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh);
+    int rc = check_shape(B, heads, T, H, W, head_dim, s, pattern, &sh, pad);
     if (rc != SKIPARSE_OK) return rc;
     if (!q8 || !k8 || !v8 || !sq || !sk || !sv || !out_bf16) return SKIPARSE_EINVAL;
     if (misaligned(q8) || misaligned(k8) || misaligned(v8) || misaligned(out_bf16)) return SKIPARSE_EINVAL;
     if (head_dim != 64 && head_dim != 128) return SKIPARSE_EUNSUPPORTED;
     rc = check_attn_ranges(sh, W, 2);
     if (rc != SKIPARSE_OK) return rc;
-    if (overlap2(out_bf16, sh.elems * 2, q8, sh.elems) || overlap2(out_bf16, sh.elems * 2, k8, sh.elems) ||
-        overlap2(out_bf16, sh.elems * 2, v8, sh.elems))
+    // the quantised tensors are addressed with 32-bit byte offsets inside one subsequence
+    if ((uint64_t)sh.n_sub * sh.row_elems >= (1ull << 32)) return SKIPARSE_ESHAPE;
+    const size_t in_bytes = sparse_elems(B, s, sh), out_bytes = sh.elems * 2;
+    if (overlap2(out_bf16, out_bytes, q8, in_bytes) || overlap2(out_bf16, out_bytes, k8, in_bytes) ||
+        overlap2(out_bf16, out_bytes, v8, in_bytes))
         return SKIPARSE_EINVAL;
     // one float per (subsequence, head, 128 positions); the kernel reads them while it writes out
     const size_t scale_bytes = (size_t)s * s * B * heads * ((sh.n_sub + 127) / 128) * sizeof(float);
     for (const float* sc : {sq, sk, sv})
-        if ((reinterpret_cast<uintptr_t>(sc) & 3u) || overlap2(out_bf16, sh.elems * 2, sc, scale_bytes)) return SKIPARSE_EINVAL;
+        if ((reinterpret_cast<uintptr_t>(sc) & 3u) || overlap2(out_bf16, out_bytes, sc, scale_bytes)) return SKIPARSE_EINVAL;
     Fp8AttnArgs a;
     a.q8 = q8; a.k8 = k8; a.v8 = v8; a.sq = sq; a.sk = sk; a.sv = sv; a.out = out_bf16;
     a.B = B; a.heads = heads; a.head_dim = head_dim;
     a.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
     a.n_blk = (uint32_t)((sh.n_sub + 127) / 128);
-    a.g = make_gridmap(T, H, W, s, pattern);
+    a.pad = pad;
+    a.g = make_gridmap(T, H, W, s, pattern, pad);
     return finish(launch_attn_fp8(a, (hipStream_t)stream));
+}
+
+int skiparse_attn_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* sq, const float* sk, const float* sv,
+                          void* out_bf16, int B, int heads, int T, int H, int W, int head_dim, int s, int pattern,
+                          float scale, void* stream) {
+    return skiparse_attn_fwd_fp8_ex(q8, k8, v8, sq, sk, sv, out_bf16, B, heads, T, H, W, head_dim, s, pattern, scale, 0u, stream);
 }
 
 const char* skiparse_strerror(int code) {

@@ -30,6 +30,7 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(2))) int i32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
@@ -48,7 +49,10 @@ __device__ inline void lane_pair_f(float x, float& lo, float& hi) {
     hi = __uint_as_float(r1);
 }
 
-template <int D>
+// PAD: any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s (the quantiser has put zero codes at the
+// padding positions); a padding position is a masked key (a -inf bias per staged row, formed a tile ahead by one wavefront and added
+// to the logits) and a skipped query.
+template <int D, bool PAD>
 __attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD8, WAVES_PER_SIMD8)))
 __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32_t q_tiles, uint32_t total, uint32_t per_xcd) {
     constexpr int NJ = D / 64;         // 64-channel MFMA steps of S^T = K Q^T
@@ -66,6 +70,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     __shared__ __attribute__((aligned(1024))) char vbuf0[TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char vbuf1[TILE_BYTES];
     __shared__ float sv_part[NW8];
+    __shared__ __attribute__((aligned(16))) float kbias[2][KT8];  // PAD only: 0 for a real key of the tile, -inf for padding
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
@@ -75,6 +80,15 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     const uint32_t unit = lin / q_tiles, qt = lin - unit * q_tiles;  // unit = sb * heads + head
     const uint32_t sb = unit / (uint32_t)a.heads, head = unit - sb * (uint32_t)a.heads;
     const uint32_t n_seq = (uint32_t)a.g.n_sub, n_blk = a.n_blk;
+    const uint32_t pq_ = sb / (uint32_t)a.B, b0_ = sb - pq_ * (uint32_t)a.B;
+    const uint32_t p_ = a.g.mode == MODE_DENSE ? 0u : pq_ / (uint32_t)a.g.s, q_ = a.g.mode == MODE_DENSE ? 0u : pq_ - p_ * (uint32_t)a.g.s;
+    // one wavefront (they take turns) marks the keys of a tile: lane = key
+    auto mark_keys = [&](uint32_t t) __attribute__((always_inline)) {
+        const uint32_t j = t * KT8 + lane;
+        bool real = false;
+        if (j < n_seq) (void)src_token_padded(a.g, p_, q_, j, &real);
+        kbias[t & 1u][lane] = real ? 0.f : -INFINITY;
+    };
     const size_t C = (size_t)a.heads * D;  // bytes per position in the sparse layout
     const size_t unit_off = ((size_t)sb * n_seq) * C + (size_t)head * D;
     const unsigned char* Qg = (const unsigned char*)a.q8 + unit_off;
@@ -97,7 +111,13 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
 
     // Q fragments: lane = query lq, 32 consecutive channels starting at 64*j + 32*h
     const uint32_t jq = qt * (32u * NW8) + wave * 32u + lq;
-    const bool q_valid = jq < n_seq;
+    bool q_valid = jq < n_seq;
+    uint32_t q_tok = 0;  // PAD: the query's token in the unpadded tensor
+    if (PAD) {
+        bool real = false;
+        q_tok = src_token_padded(a.g, p_, q_, q_valid ? jq : 0u, &real);
+        q_valid = q_valid && real;
+    }
     const size_t q_off = (size_t)(q_valid ? jq : n_seq - 1u) * C;
     i32x8 qf[NJ];
 #pragma unroll
@@ -147,6 +167,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
 
     const uint32_t n_kt = (n_seq + KT8 - 1) / KT8;
     issue_tile(0, kbuf0, vbuf0);
+    if (PAD && wave == 0) mark_keys(0);
     tile_landed();
     __syncthreads();
 
@@ -163,6 +184,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
         // the next tile's loads have the whole tile to land (enqueued after the QK products instead: 13 % slower; one workgroup of
         // 12 wavefronts sharing a tile instead of three independent ones of 4: 7 % slower)
         if (more) issue_tile(t + 1, PARITY ? kbuf0 : kbuf1, PARITY ? vbuf0 : vbuf1);
+        if (PAD && more && wave == ((t + 1u) & (uint32_t)(NW8 - 1))) mark_keys(t + 1u);  // read after this tile's closing barrier
         const float ct = cq * sk_cur;        // logits -> log2 units for this key block
         const float pg = sv_cur * p_gain;    // V scale of this key block, relative to the largest, times the gain
         {   // the next tile's scales are fetched a tile ahead so that no tile waits for them
@@ -186,7 +208,16 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
                 sacc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[j], sacc[kt], 0, 0, 0, 0, 0, 0);
             }
         }
-        if (LAST && (n_seq % KT8) != 0) {
+        if (PAD) {  // register r of block kt is key 32*kt + 8*(r/4) + 4*h + r%4; positions past the end carry -inf as well
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const f32x4 b4 = *(const f32x4*)&kbias[PARITY][kt * 32 + 8 * i + 4 * h];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) sacc[kt][4 * i + e] += b4[e];
+                }
+        } else if (LAST && (n_seq % KT8) != 0) {
 #pragma unroll
             for (int kt = 0; kt < 2; kt++)
 #pragma unroll
@@ -242,9 +273,11 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
             float lo, hi;
             lane_pair_f(mx, lo, hi);
             const float m_new = fmaxf(m_ref, fmaxf(lo, hi) * ct);
-            alpha = __builtin_amdgcn_exp2f(m_ref - m_new);  // 0 on the first tile
+            // a tile of nothing but padding before any real key (any-resolution mode): the reference stays -inf, nothing to rescale,
+            // and the exponentials are taken against 0 so that the masked logits give exp2(-inf) = 0
+            alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);  // 0 on the first tile with a real key
             m_ref = m_new;
-            lsum = probs(m_ref - lg, pb);  // now every probability is at most the gain (<= 16)
+            lsum = probs(m_new == -INFINITY ? -lg : m_ref - lg, pb);  // now every probability is at most the gain (<= 16)
             rescale = true;
         }
         l_run = fmaf(l_run, alpha, lsum * inv_pg);
@@ -290,9 +323,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     lane_pair_f(l_run, llo, lhi);
     const float inv = sv_max / (P_GAIN * (llo + lhi));
     if (q_valid) {
-        const uint32_t pq = sb / (uint32_t)a.B, b0 = sb - pq * (uint32_t)a.B;
-        const uint32_t p = a.g.mode == MODE_DENSE ? 0u : pq / (uint32_t)a.g.s, q = a.g.mode == MODE_DENSE ? 0u : pq - p * (uint32_t)a.g.s;
-        const size_t row = (size_t)b0 * (uint32_t)a.g.n_tok + src_token(a.g, p, q, jq);
+        const size_t row = (size_t)b0_ * (uint32_t)a.g.n_tok + (PAD ? q_tok : src_token(a.g, p_, q_, jq));
         __bf16* orow = (__bf16*)a.out + row * C + (size_t)head * D;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
@@ -306,7 +337,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     }
 }
 
-template <int D>
+template <int D, bool PAD>
 static hipError_t launch_fp8_t(const Fp8AttnArgs& a, hipStream_t stream) {
     const uint32_t s2 = a.g.mode == MODE_DENSE ? 1u : (uint32_t)(a.g.s * a.g.s);
     const uint32_t n_units = (uint32_t)a.B * s2 * (uint32_t)a.heads;
@@ -314,13 +345,13 @@ static hipError_t launch_fp8_t(const Fp8AttnArgs& a, hipStream_t stream) {
     const uint64_t total = (uint64_t)n_units * q_tiles;
     if (total > 0x7ffffff0ull) return hipErrorInvalidConfiguration;
     const uint32_t per_xcd = (uint32_t)((total + 7u) / 8u);
-    attn_fwd_fp8_kernel<D><<<8u * per_xcd, NT8, 0, stream>>>(a, q_tiles, (uint32_t)total, per_xcd);
+    attn_fwd_fp8_kernel<D, PAD><<<8u * per_xcd, NT8, 0, stream>>>(a, q_tiles, (uint32_t)total, per_xcd);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_fp8(const Fp8AttnArgs& a, hipStream_t stream) {
-    if (a.head_dim == 128) return launch_fp8_t<128>(a, stream);
-    if (a.head_dim == 64) return launch_fp8_t<64>(a, stream);
+    if (a.head_dim == 128) return a.pad ? launch_fp8_t<128, true>(a, stream) : launch_fp8_t<128, false>(a, stream);
+    if (a.head_dim == 64) return a.pad ? launch_fp8_t<64, true>(a, stream) : launch_fp8_t<64, false>(a, stream);
     return hipErrorInvalidValue;
 }
 

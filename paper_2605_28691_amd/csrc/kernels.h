@@ -66,7 +66,7 @@ struct BwdArgs {
 hipError_t launch_attn_bwd_bf16(const BwdArgs& a, hipStream_t stream);
 
 // bf16 (original layout) -> E4M3 codes (sparse layout) + one float32 scale per (subsequence, head, 128 positions).
-hipError_t launch_quantize_fp8(const void* x, void* x8, float* scales, int B, int heads, int head_dim, const GridMap& g,
+hipError_t launch_quantize_fp8(const void* x, void* x8, float* scales, int B, int heads, int head_dim, const GridMap& g, bool pad,
                                hipStream_t stream);
 
 // FP8 flash-attention forward on the quantised sparse-layout tensors; bf16 output in the original layout.
@@ -83,6 +83,7 @@ struct Fp8AttnArgs {
     int head_dim;
     float scale;
     uint32_t n_blk;   // scale blocks per (subsequence, head): ceil(n_sub / 128)
+    bool pad;         // any-resolution mode: g describes the padded grid; padding positions are masked keys and skipped queries
     GridMap g;
 };
 hipError_t launch_attn_fp8(const Fp8AttnArgs& a, hipStream_t stream);

@@ -14,7 +14,9 @@ typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 constexpr int QBLOCK = 128;  // positions per scale block
 
-template <int D>
+// PAD: any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s; a padding position is a row of zero
+// codes and does not enter the block's maximum.
+template <int D, bool PAD>
 __global__ __launch_bounds__(256) void quantize_fp8_kernel(const unsigned short* __restrict__ x, unsigned char* __restrict__ x8,
                                                            float* __restrict__ scales, int B, int heads, GridMap g, uint32_t n_blk) {
     constexpr int CH = D / 8;                    // 16-byte chunks per row segment
@@ -37,8 +39,12 @@ __global__ __launch_bounds__(256) void quantize_fp8_kernel(const unsigned short*
         const uint32_t j = blk * QBLOCK + r0 + ps * ROWS_PER_PASS;
         v[ps] = u32x4{0u, 0u, 0u, 0u};
         if (j < n_sub) {
-            const size_t row = (size_t)b * (uint32_t)g.n_tok + src_token(g, p, q, j);
-            v[ps] = __builtin_nontemporal_load((const u32x4*)(x + row * C + (size_t)head * D) + c);
+            bool real = true;
+            const uint32_t tok = PAD ? src_token_padded(g, p, q, j, &real) : src_token(g, p, q, j);
+            if (real) {
+                const size_t row = (size_t)b * (uint32_t)g.n_tok + tok;
+                v[ps] = __builtin_nontemporal_load((const u32x4*)(x + row * C + (size_t)head * D) + c);
+            }
         }
 #pragma unroll
         for (int e = 0; e < 4; e++) {
@@ -74,16 +80,22 @@ __global__ __launch_bounds__(256) void quantize_fp8_kernel(const unsigned short*
     }
 }
 
-hipError_t launch_quantize_fp8(const void* x, void* x8, float* scales, int B, int heads, int head_dim, const GridMap& g,
+hipError_t launch_quantize_fp8(const void* x, void* x8, float* scales, int B, int heads, int head_dim, const GridMap& g, bool pad,
                                hipStream_t stream) {
     const uint32_t s2 = g.mode == MODE_DENSE ? 1u : (uint32_t)(g.s * g.s);
     const uint32_t n_blk = ((uint32_t)g.n_sub + QBLOCK - 1) / QBLOCK;
     const uint64_t blocks = (uint64_t)B * s2 * (uint32_t)heads * n_blk;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    if (head_dim == 128)
-        quantize_fp8_kernel<128><<<(uint32_t)blocks, 256, 0, stream>>>((const unsigned short*)x, (unsigned char*)x8, scales, B, heads, g, n_blk);
+    const unsigned short* xs = (const unsigned short*)x;
+    unsigned char* x8c = (unsigned char*)x8;
+    if (head_dim == 128 && pad)
+        quantize_fp8_kernel<128, true><<<(uint32_t)blocks, 256, 0, stream>>>(xs, x8c, scales, B, heads, g, n_blk);
+    else if (head_dim == 128)
+        quantize_fp8_kernel<128, false><<<(uint32_t)blocks, 256, 0, stream>>>(xs, x8c, scales, B, heads, g, n_blk);
+    else if (head_dim == 64 && pad)
+        quantize_fp8_kernel<64, true><<<(uint32_t)blocks, 256, 0, stream>>>(xs, x8c, scales, B, heads, g, n_blk);
     else if (head_dim == 64)
-        quantize_fp8_kernel<64><<<(uint32_t)blocks, 256, 0, stream>>>((const unsigned short*)x, (unsigned char*)x8, scales, B, heads, g, n_blk);
+        quantize_fp8_kernel<64, false><<<(uint32_t)blocks, 256, 0, stream>>>(xs, x8c, scales, B, heads, g, n_blk);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

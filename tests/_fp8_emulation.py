@@ -77,3 +77,51 @@ def ideal_attention_rows(q, k, v, rows, T, H, W, s, pattern, scale):
         idx = [i for i, _ in lst]
         out[idx] = ideal_unit(q8, sq, k8, sk, v8, sv, sb, hd, scale, positions=[j for _, j in lst])
     return out
+
+
+# ---- any-resolution mode (Sec. 3.2): positions run over the grid padded to multiples of s*s; padding positions are zero codes, masked
+# as keys and skipped as queries.
+
+
+def padded_positions(B, T, H, W, s, pattern):
+    """tok_at[sb][j] = token number (in the unpadded tensor) at position j of subsequence sb of the padded grid, -1 for padding;
+    from the oracle's permute applied to the token numbers of the zero-padded grid."""
+    u = s * s
+    Hp, Wp = (H + u - 1) // u * u, (W + u - 1) // u * u
+    ids = np.arange(T * H * W, dtype=np.int64).reshape(1, T, H, W)
+    ids = np.pad(ids, ((0, 0), (0, 0), (0, Hp - H), (0, Wp - W)), constant_values=-1)
+    ids = np.repeat(ids, B, axis=0).reshape(B, T * Hp * Wp, 1)
+    return oracle.permute(ids, T, Hp, Wp, s, pattern)[:, :, 0]
+
+
+def ideal_attention_rows_padded(q, k, v, rows, T, H, W, s, pattern, scale):
+    """rows[i] = (b, head, n) of REAL tokens -> [len(rows)][D]: the ideal-E4M3 pipeline on the padded quantised tensors with the
+    padding positions masked as keys."""
+    (q8, sq), (k8, sk), (v8, sv) = (oracle.quantize_fp8_padded(t, T, H, W, s, pattern) for t in (q, k, v))
+    B = q.shape[0]
+    tok_at = padded_positions(B, T, H, W, s, pattern)     # [s*s*B][Nsub_padded]
+    rows = np.asarray(rows, dtype=np.int64).reshape(-1, 3)
+    # inverse map: (batch element, token) -> (subsequence, position); subsequence sb belongs to batch element sb % B
+    inv = np.full((B, T * H * W, 2), -1, dtype=np.int64)
+    for sb in range(tok_at.shape[0]):
+        js = np.flatnonzero(tok_at[sb] >= 0)
+        inv[sb % B, tok_at[sb, js], 0] = sb
+        inv[sb % B, tok_at[sb, js], 1] = js
+    assert (inv >= 0).all()  # every real token sits at exactly one position
+    where = {}
+    for i, (b, hd, n) in enumerate(rows):
+        where.setdefault((int(inv[b, n, 0]), int(hd)), []).append((i, int(inv[b, n, 1])))
+    out = np.empty((rows.shape[0], q.shape[3]), dtype=np.float64)
+    for (sb, hd), lst in where.items():
+        real = tok_at[sb] >= 0
+        qd = dequantised_unit(q8, sq, sb, hd)[[j for _, j in lst]]
+        kd = dequantised_unit(k8, sk, sb, hd)
+        vcodes = oracle.e4m3_decode_array(v8[sb, :, hd, :])
+        svb = sv[sb, hd, np.arange(v8.shape[1]) // BLOCK].astype(np.float64)
+        sv_max = float(sv[sb, hd].max())
+        S = scale * (qd @ kd.T)
+        S[:, ~real] = -np.inf
+        P = np.exp(S - S.max(axis=1, keepdims=True))
+        P8 = e4m3_round(P * (svb / sv_max * P_GAIN)[None, :])
+        out[[i for i, _ in lst]] = (P8 @ vcodes) * (sv_max / P_GAIN) / P.sum(axis=1, keepdims=True)
+    return out

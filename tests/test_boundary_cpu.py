@@ -47,7 +47,8 @@ def test_every_declared_symbol_is_exported(lib):
             "skiparse_quantize_fp8", "skiparse_attn_fwd_fp8", "skiparse_strerror", "skiparse_last_hip_error",
             "skiparse_switch_pattern", "skiparse_attn_fwd_sparse", "skiparse_attn_fwd_lse",
             "skiparse_bwd_workspace_bytes", "skiparse_attn_bwd", "skiparse_lse_bytes", "skiparse_attn_bwd_static",
-            "skiparse_static_scratch_bytes", "skiparse_ssp_pack", "skiparse_ssp_unpack"} <= set(names)
+            "skiparse_static_scratch_bytes", "skiparse_ssp_pack", "skiparse_ssp_unpack",
+            "skiparse_quantize_fp8_ex", "skiparse_attn_fwd_fp8_ex"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert not [n for n in names if "probe" in n]  # the measurement kernels live in a library of their own
@@ -258,3 +259,17 @@ def test_ssp_entry_points_reject_bad_arguments(lib):
         assert fn(p, q, 1, 2, 2, 8, 8, 64, 2, 0, 0, None) == -1
         assert fn(p, q, 1, 2, 2, 8, 8, 64, 2, 2, 7, None) == -1             # unknown element type
         assert fn(ctypes.c_void_p(FAKE + 8), q, *ok, None) == -1            # misaligned
+
+
+def test_fp8_flagged_entry_points(lib):
+    """The any-resolution flag admits grids that the plain calls refuse; unknown flags are refused."""
+    a = [ctypes.c_void_p(FAKE + i * (1 << 30)) for i in range(8)]
+    f = ctypes.c_float(0.0)
+    assert lib.skiparse_quantize_fp8(a[0], a[1], a[2], 1, 2, 2, 7, 9, 64, 2, 0, None) == -2
+    assert lib.skiparse_quantize_fp8_ex(a[0], a[1], a[2], 1, 2, 2, 7, 9, 64, 2, 0, 4, None) == -1       # unknown flag
+    assert lib.skiparse_quantize_fp8_ex(None, a[1], a[2], 1, 2, 2, 7, 9, 64, 2, 0, 2, None) == -1       # shape accepted, pointer refused
+    assert lib.skiparse_quantize_fp8_ex(a[0], a[1], a[2], 1, 2, 2, 7, 9, 96, 2, 0, 2, None) == -3       # head_dim 96
+    assert lib.skiparse_attn_fwd_fp8(a[0], a[1], a[2], a[3], a[4], a[5], a[6], 1, 2, 2, 7, 9, 64, 2, 1, f, None) == -2
+    assert lib.skiparse_attn_fwd_fp8_ex(a[0], a[1], a[2], a[3], a[4], a[5], a[6], 1, 2, 2, 7, 9, 64, 2, 1, f, 1, None) == -1   # SKIPARSE_FUSED is no flag here
+    assert lib.skiparse_attn_fwd_fp8_ex(a[0], a[1], a[2], a[3], a[4], None, a[6], 1, 2, 2, 7, 9, 64, 2, 1, f, 2, None) == -1
+    assert lib.skiparse_attn_fwd_fp8_ex(a[0], a[1], a[2], a[3], a[4], a[5], a[0], 1, 2, 2, 7, 9, 64, 2, 1, f, 2, None) == -1   # out aliases q8

@@ -62,3 +62,25 @@ def test_format_floor_on_gaussian_inputs_and_with_channel_means():
     exact = oracle.skiparse_attention(*oracle_inputs(q, k, vm), T, H, W, s, "group", w.scale)
     ma, rl = errors(emu.ideal_attention(*oracle_inputs(q, k, vm), T, H, W, s, "group", w.scale), exact)
     assert rl < 1e-2 and ma < 6e-2
+
+
+def test_padded_emulation_equals_the_plain_one_on_a_divisible_grid_and_masks_padding_elsewhere():
+    w = si.make_shape("ep", 1, 2, 64, 3, 8, 8, 2, seed=36)
+    q, k, v = si.make_qkv(w)
+    rows = si.sample_rows(w, 10, seed=2)
+    a = emu.ideal_attention_rows_padded(*oracle_inputs(q, k, v), rows, 3, 8, 8, 2, "group", w.scale)
+    b = emu.ideal_attention_rows(*oracle_inputs(q, k, v), rows, 3, 8, 8, 2, "group", w.scale)
+    assert np.array_equal(a, b)
+    # a grid that needs padding: every real token sits at exactly one position, padding positions are -1
+    tok = emu.padded_positions(2, 3, 5, 7, 2, "token")
+    assert tok.shape == (8, 3 * 8 * 8 // 4)
+    for b_ in range(2):
+        real = np.sort(tok[b_::2][tok[b_::2] >= 0])
+        assert np.array_equal(real, np.arange(3 * 5 * 7))
+    # and the emulation stays on the format's floor there as well
+    w2 = si.make_shape("ep2", 1, 2, 128, 9, 17, 21, 2, seed=35)
+    q, k, v = si.make_qkv(w2)
+    rows = si.sample_rows(w2, 40, seed=1)
+    exact = oracle.skiparse_attention_rows_padded(*oracle_inputs(q, k, v), rows, 9, 17, 21, 2, "token", w2.scale)
+    _, rl = errors(emu.ideal_attention_rows_padded(*oracle_inputs(q, k, v), rows, 9, 17, 21, 2, "token", w2.scale), exact)
+    assert 3.5e-2 < rl < 7e-2
