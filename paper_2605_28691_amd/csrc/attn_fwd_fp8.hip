@@ -71,6 +71,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
     __shared__ __attribute__((aligned(1024))) char vbuf1[TILE_BYTES];
     __shared__ float sv_part[NW8];
     __shared__ __attribute__((aligned(16))) float kbias[2][KT8];  // PAD only: 0 for a real key of the tile, -inf for padding
+    __shared__ uint32_t kany[2];                                  // PAD only: non-zero if the tile holds any padding (most hold none)
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lq = lane & 31u, h = lane >> 5;
@@ -88,6 +89,8 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
         bool real = false;
         if (j < n_seq) (void)src_token_padded(a.g, p_, q_, j, &real);
         kbias[t & 1u][lane] = real ? 0.f : -INFINITY;
+        const unsigned long long pads = __builtin_amdgcn_ballot_w64(!real);
+        if (lane == 0) kany[t & 1u] = pads != 0 ? 1u : 0u;
     };
     const size_t C = (size_t)a.heads * D;  // bytes per position in the sparse layout
     const size_t unit_off = ((size_t)sb * n_seq) * C + (size_t)head * D;
@@ -208,7 +211,8 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
                 sacc[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf, qf[j], sacc[kt], 0, 0, 0, 0, 0, 0);
             }
         }
-        if (PAD) {  // register r of block kt is key 32*kt + 8*(r/4) + 4*h + r%4; positions past the end carry -inf as well
+        if (PAD && __builtin_amdgcn_readfirstlane(kany[PARITY]) != 0) {
+            // register r of block kt is key 32*kt + 8*(r/4) + 4*h + r%4; positions past the end carry -inf as well
 #pragma unroll
             for (int kt = 0; kt < 2; kt++)
 #pragma unroll
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(NT8) void attn_fwd_fp8_kernel(Fp8AttnArgs a, uint32
 #pragma unroll
                     for (int e = 0; e < 4; e++) sacc[kt][4 * i + e] += b4[e];
                 }
-        } else if (LAST && (n_seq % KT8) != 0) {
+        } else if (!PAD && LAST && (n_seq % KT8) != 0) {
 #pragma unroll
             for (int kt = 0; kt < 2; kt++)
 #pragma unroll
